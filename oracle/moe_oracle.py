@@ -1,0 +1,272 @@
+"""CPU oracle for the MoE FFN layer forward -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+A plain, slow, fp64 numpy implementation of what the layer computes, written
+from the paper's description of an MoE FFN layer (Section 2.1 and Fig. 1: a
+gating network scores every (token, expert) pair, each token goes to its
+top-k experts, each expert is linear -> activation -> linear, and the expert
+outputs are combined and put back in the original token order) and of the
+hot/cold expert split (Section 3.3: the H experts with the highest load form
+the hot set; "activated" experts are those with at least one token).
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this
+module.  It shares no code with the HIP path and imports nothing from it.
+
+Because the sparse layer equals its dense definition exactly (up to rounding
+order), the oracle is that definition written out; `layer_bruteforce` is the
+"every expert on every token, select afterwards" form used to cross-check it.
+
+Parity status: no numeric layer output is printed anywhere in the paper, so
+absolute values are pinned through brute force, closed-form special cases,
+a hand-derived worked example, invariants and metamorphic relations (see
+tests).  The gate-weighting rule (probability of the chosen expert, optionally
+renormalised over the chosen k) is a reading of "outputs are combined"
+(Section 2.1), which the paper leaves open: in that sense `gate_weights` is
+"parity unpinned" with respect to the paper's text.
+
+Conventions: T tokens, d = d_model, f = d_ff, E experts, k experts per token,
+A = T*k assignments, flat assignment id a = t*k + j (slot j = 0 is the best
+expert).  Weight matrices are [out_features, in_features].
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+def gate_logits(x, w_gate, b_gate=None):
+    """L[t,e] = sum_i x[t,i] * w_gate[e,i] (+ b[e]).  Section 2.1: the gating
+    function scores each token against every expert."""
+    L = np.asarray(x, F64) @ np.asarray(w_gate, F64).T
+    if b_gate is not None:
+        L = L + np.asarray(b_gate, F64)[None, :]
+    return L
+
+
+def softmax_rows(L):
+    """Probability distribution over the experts for each token (Section 2.1)."""
+    L = np.asarray(L, F64)
+    z = np.exp(L - L.max(axis=1, keepdims=True))
+    return z / z.sum(axis=1, keepdims=True)
+
+
+def topk_experts(L, k):
+    """idx[t, j] = expert with the (j+1)-th largest logit of token t; equal
+    logits are ordered by lowest expert index.  Selection is made on logits
+    (softmax is monotone, so the order is the same as on probabilities)."""
+    L = np.array(L, F64, copy=True)
+    T, E = L.shape
+    assert 1 <= k <= E
+    idx = np.empty((T, k), np.int32)
+    rows = np.arange(T)
+    for j in range(k):
+        best = np.argmax(L, axis=1)          # first maximum = lowest index
+        idx[:, j] = best
+        L[rows, best] = -np.inf
+    return idx
+
+
+def topk_margin(L, k):
+    """Smallest gap between consecutive entries of the k+1 largest logits of each
+    token (k largest if k == E).  A token whose margin is tiny can legitimately be
+    routed differently by a lower-precision implementation."""
+    L = np.asarray(L, F64)
+    E = L.shape[1]
+    n = min(k + 1, E)
+    top = -np.sort(-L, axis=1)[:, :n]
+    if n == 1:
+        return np.full(L.shape[0], np.inf)
+    return np.min(top[:, :-1] - top[:, 1:], axis=1)
+
+
+def gate_weights(p, idx, renormalize):
+    """g[t,j] = p[t, idx[t,j]], divided by the sum over the chosen k when
+    `renormalize` (top-2 NLLB-style); raw probability otherwise (Switch-style
+    top-1: the output is scaled by the router probability)."""
+    p = np.asarray(p, F64)
+    g = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    if renormalize:
+        g = g / g.sum(axis=1, keepdims=True)
+    return g
+
+
+def expert_histogram(idx, E):
+    """counts[e] = number of assignments routed to e; offsets = exclusive prefix
+    sum with offsets[E] = A.  Drop-less, padding-less routing (Section 4.1):
+    every assignment is kept, nothing is padded."""
+    counts = np.zeros(E, np.int32)
+    for e in np.asarray(idx).reshape(-1):
+        counts[e] += 1
+    offsets = np.zeros(E + 1, np.int32)
+    for e in range(E):
+        offsets[e + 1] = offsets[e] + counts[e]
+    return counts, offsets
+
+
+def activated_experts(counts):
+    """Number of experts with at least one token (Section 3.3, Expert_Activ)."""
+    return int(np.count_nonzero(np.asarray(counts) > 0))
+
+
+def stable_permutation(idx, E):
+    """perm[p] = flat assignment id sitting at sorted position p when assignments
+    are grouped by expert (experts ascending; inside an expert, ascending flat id);
+    inv_perm[a] = position of assignment a."""
+    flat = np.asarray(idx).reshape(-1)
+    A = flat.shape[0]
+    perm = np.empty(A, np.int32)
+    pos = 0
+    for e in range(E):
+        for a in range(A):
+            if flat[a] == e:
+                perm[pos] = a
+                pos += 1
+    assert pos == A
+    inv = np.empty(A, np.int32)
+    for p in range(A):
+        inv[perm[p]] = p
+    return perm, inv
+
+
+def stable_permutation_fast(idx, E):
+    """Same result as `stable_permutation` through numpy's stable sort; used where
+    A is too large for the double loop (checked against it in the tests)."""
+    flat = np.asarray(idx).reshape(-1)
+    perm = np.argsort(flat, kind="stable").astype(np.int32)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(flat.shape[0], dtype=np.int32)
+    return perm, inv
+
+
+def hot_mask_top_h(counts, H):
+    """mask[e] = 1 for the H experts with the largest token counts (Section 3.3:
+    the top-H most loaded experts are the hot set); equal counts are ordered by
+    lowest expert index.  H is clipped to [0, E]."""
+    counts = np.asarray(counts)
+    E = counts.shape[0]
+    H = max(0, min(int(H), E))
+    c = counts.astype(np.int64).copy()
+    mask = np.zeros(E, np.uint8)
+    for _ in range(H):
+        e = int(np.argmax(c))
+        mask[e] = 1
+        c[e] = -1
+    return mask
+
+
+def round_bf16(a):
+    """Round fp64 values to the nearest bfloat16 (8 significant bits, ties to even),
+    returned as fp64.  Written from the format's definition (sign, 8 exponent bits,
+    7 stored mantissa bits); overflow and subnormals are not handled because the
+    oracle only applies it to hidden activations of moderate size."""
+    a = np.asarray(a, F64)
+    m, e = np.frexp(a)                 # a = m * 2**e, 0.5 <= |m| < 1
+    q = np.rint(m * 256.0) / 256.0     # keep 8 significant bits; rint = ties to even
+    return np.ldexp(q, e)
+
+
+def expert_ffn(X_e, W1_e, W2_e, h_dtype=None):
+    """Y = relu(X W1^T) W2^T for one expert (Section 2.1: two linear layers with an
+    activation in between; Section 3.4: a gemm with a trailing ReLU, then a gemm).
+    W1_e [f, d], W2_e [d, f]; no biases.
+
+    h_dtype = None keeps the hidden activation in fp64 (the exact definition).
+    h_dtype = "bf16" rounds it once to bfloat16 before the second product, which is
+    what a bfloat16 inference run (Section 4.1) stores between the two linear layers;
+    all sums stay in fp64."""
+    h = np.asarray(X_e, F64) @ np.asarray(W1_e, F64).T
+    h = np.maximum(h, 0.0)
+    if h_dtype == "bf16":
+        h = round_bf16(h)
+    elif h_dtype not in (None, "f32", "f64"):
+        raise ValueError(h_dtype)
+    return h @ np.asarray(W2_e, F64).T
+
+
+def permute_tokens(x, perm, k):
+    """x_perm[p] = x[perm[p] // k]: token rows in expert-contiguous order."""
+    return np.asarray(x)[np.asarray(perm) // k]
+
+
+def combine(y_perm, inv_perm, idx, g, mask=None):
+    """out[t] = sum_j [mask[idx[t,j]]] * g[t,j] * y_perm[inv_perm[t*k+j]]
+    (Section 2.1: outputs are combined and restored to the original token order).
+    Rows of y_perm that belong to masked-out experts are never read."""
+    T, k = idx.shape
+    d = y_perm.shape[1]
+    out = np.zeros((T, d), F64)
+    for t in range(T):
+        for j in range(k):
+            e = idx[t, j]
+            if mask is not None and not mask[e]:
+                continue
+            out[t] += g[t, j] * np.asarray(y_perm[inv_perm[t * k + j]], F64)
+    return out
+
+
+def route(x, w_gate, b_gate, k, renormalize):
+    """Steps 1-2 of the layer: logits, softmax, top-k, gate weights, histogram."""
+    L = gate_logits(x, w_gate, b_gate)
+    p = softmax_rows(L)
+    idx = topk_experts(L, k)
+    g = gate_weights(p, idx, renormalize)
+    counts, offsets = expert_histogram(idx, w_gate.shape[0])
+    return dict(logits=L, probs=p, idx=idx, g=g, counts=counts, offsets=offsets,
+                margin=topk_margin(L, k))
+
+
+def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
+                  return_intermediates=False, h_dtype=None):
+    """Whole MoE FFN layer.  `expert(e)` returns (W1_e, W2_e); it is called only for
+    experts that received tokens and are not masked out.  With a mask, only the
+    masked-in experts' share of the output is produced (Section 3.3: hot experts
+    on one device, the rest elsewhere; gates are fixed before the split)."""
+    x = np.asarray(x, F64)
+    E = w_gate.shape[0]
+    r = route(x, w_gate, b_gate, k, renormalize)
+    idx, g, offsets = r["idx"], r["g"], r["offsets"]
+    perm, inv = stable_permutation_fast(idx, E)
+    x_perm = permute_tokens(x, perm, k)
+    y_perm = np.zeros((perm.shape[0], x.shape[1]), F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo or (mask is not None and not mask[e]):
+            continue
+        W1_e, W2_e = expert(e)
+        y_perm[lo:hi] = expert_ffn(x_perm[lo:hi], W1_e, W2_e, h_dtype)
+    out = combine(y_perm, inv, idx, g, mask)
+    if return_intermediates:
+        r.update(perm=perm, inv_perm=inv, x_perm=x_perm, y_perm=y_perm, out=out)
+        return r
+    return out
+
+
+def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None):
+    """Dense definition: run every expert on every token, then keep each token's
+    top-k experts, weight and sum.  Tiny inputs only."""
+    x = np.asarray(x, F64)
+    T, d = x.shape
+    E = w_gate.shape[0]
+    Yall = np.empty((T, E, d), F64)
+    for e in range(E):
+        Yall[:, e, :] = expert_ffn(x, W1[e], W2[e])
+    L = gate_logits(x, w_gate, b_gate)
+    p = softmax_rows(L)
+    idx = topk_experts(L, k)
+    g = gate_weights(p, idx, renormalize)
+    out = np.zeros((T, d), F64)
+    for t in range(T):
+        for j in range(k):
+            e = idx[t, j]
+            if mask is None or mask[e]:
+                out[t] += g[t, j] * Yall[t, e]
+    return out
+
+
+def rel_error(got, ref):
+    """Element-wise |got-ref| / max(|ref|, rms(ref)); the value-parity statistic."""
+    ref = np.asarray(ref, F64)
+    got = np.asarray(got, F64)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    den = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
+    return np.abs(got - ref) / den

@@ -1,0 +1,269 @@
+"""Pins for the CPU oracle: what the paper's definition and plain mathematics fix.
+
+None of these compares the oracle with itself through the same code path: they use
+brute force over all experts, a hand-derived rational example, closed-form special
+cases that reduce to a plain matmul, invariants and metamorphic relations.
+"""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moe_oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny(T=5, d=6, f=10, E=3, k=2, seed=7, bias=False):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d))
+    wg = rng.standard_normal((E, d))
+    b = rng.standard_normal(E) if bias else None
+    W1 = rng.standard_normal((E, f, d)) / np.sqrt(d)
+    W2 = rng.standard_normal((E, d, f)) / np.sqrt(f)
+    return x, wg, b, W1, W2
+
+
+def run(x, wg, b, W1, W2, k, renorm, mask=None, **kw):
+    return orc.layer_forward(x, wg, b, lambda e: (W1[e], W2[e]), k, renorm, mask, **kw)
+
+
+# ---------------------------------------------------------------- worked example
+def _frac(a):
+    return np.array([[float(Fraction(n, d)) for n, d in row] for row in a])
+
+
+def test_worked_example_fig1_shape():
+    g = json.load(open(os.path.join(GOLD, "worked_example.json")))
+    x = np.array(g["x"], float)
+    wg = np.log(np.array(g["w_gate_log_of"], float))
+    W1 = np.array(g["W1"], float)
+    W2 = np.array(g["W2"], float)
+    r = run(x, wg, None, W1, W2, 2, True, return_intermediates=True)
+    assert np.allclose(r["probs"], _frac(g["probs_num_den"]), atol=1e-15)
+    assert r["idx"].tolist() == g["topk_idx"]
+    assert np.allclose(r["g"], _frac(g["gates_renorm_num_den"]), atol=1e-15)
+    assert r["counts"].tolist() == g["counts"]
+    assert r["offsets"].tolist() == g["offsets"]
+    assert r["perm"].tolist() == g["perm"]
+    assert r["inv_perm"].tolist() == g["inv_perm"]
+    assert np.allclose(r["out"], _frac(g["out_top2_renorm_num_den"]), atol=1e-14)
+    assert np.allclose(run(x, wg, None, W1, W2, 2, False),
+                       _frac(g["out_top2_raw_num_den"]), atol=1e-14)
+    assert np.allclose(run(x, wg, None, W1, W2, 1, False),
+                       _frac(g["out_top1_raw_num_den"]), atol=1e-14)
+    mask = orc.hot_mask_top_h(r["counts"], 1)
+    assert mask.tolist() == g["hot_mask_H1"]
+    assert np.allclose(run(x, wg, None, W1, W2, 2, True, mask),
+                       _frac(g["out_top2_renorm_hot_only_num_den"]), atol=1e-14)
+    m = np.log([a / b for a, b in g["margin_log_of_ratio"]])
+    assert np.allclose(r["margin"], m, atol=1e-14)
+    # the permutation and the slow definition agree on this case too
+    p2, i2 = orc.stable_permutation(r["idx"], 3)
+    assert p2.tolist() == g["perm"] and i2.tolist() == g["inv_perm"]
+    assert orc.activated_experts(r["counts"]) == 3
+
+
+# ---------------------------------------------------------------- brute force
+@pytest.mark.parametrize("T,d,f,E,k,renorm,bias", [
+    (5, 6, 10, 3, 2, True, False),      # Fig. 1's shape
+    (5, 6, 10, 3, 2, False, True),
+    (9, 4, 7, 5, 1, False, False),
+    (9, 4, 7, 5, 3, True, True),
+    (1, 3, 2, 2, 2, True, False),
+])
+def test_sparse_equals_dense_bruteforce(T, d, f, E, k, renorm, bias):
+    x, wg, b, W1, W2 = tiny(T, d, f, E, k, seed=T * 31 + E, bias=bias)
+    a = run(x, wg, b, W1, W2, k, renorm)
+    bf = orc.layer_bruteforce(x, wg, b, W1, W2, k, renorm)
+    assert np.allclose(a, bf, rtol=0, atol=1e-12)
+    mask = (np.arange(E) % 2).astype(np.uint8)
+    assert np.allclose(run(x, wg, b, W1, W2, k, renorm, mask),
+                       orc.layer_bruteforce(x, wg, b, W1, W2, k, renorm, mask), atol=1e-12)
+
+
+def test_bruteforce_on_tiny_preset():
+    cfg = wl.CONFIGS["tiny_f32"]
+    L = wl.make_layer(cfg)
+    W1, W2 = L.all_experts()
+    a = orc.layer_forward(L.x, L.w_gate, L.b_gate, L.expert, cfg.k, cfg.renormalize)
+    bf = orc.layer_bruteforce(L.x, L.w_gate, L.b_gate, W1, W2, cfg.k, cfg.renormalize)
+    assert np.allclose(a, bf, atol=1e-12)
+
+
+# ---------------------------------------------------------------- invariants
+@pytest.mark.parametrize("name", ["tiny_f32", "switch_base", "nllb_decode"])
+def test_routing_invariants(name):
+    cfg = wl.CONFIGS[name]
+    x = wl.make_activations(cfg)
+    wg, b = wl.make_gate(cfg)
+    r = orc.route(x, wg, b, cfg.k, cfg.renormalize)
+    idx, g, counts, offsets = r["idx"], r["g"], r["counts"], r["offsets"]
+    A = cfg.T * cfg.k
+    assert counts.sum() == A and offsets[0] == 0 and offsets[-1] == A
+    assert np.all(np.diff(offsets) == counts)
+    assert np.array_equal(counts, np.bincount(idx.reshape(-1), minlength=cfg.E))
+    perm, inv = orc.stable_permutation_fast(idx, cfg.E)
+    assert np.array_equal(np.sort(perm), np.arange(A))           # bijection
+    assert np.array_equal(perm[inv], np.arange(A))
+    keys = idx.reshape(-1)[perm]
+    assert np.all(np.diff(keys) >= 0)                            # expert-contiguous
+    same = np.diff(keys) == 0
+    assert np.all(np.diff(perm)[same] > 0)                       # stable inside an expert
+    # gates are the softmax probabilities of the chosen experts
+    p = r["probs"]
+    assert np.allclose(p.sum(1), 1, atol=1e-12)
+    chosen = np.take_along_axis(p, idx.astype(np.int64), 1)
+    if cfg.renormalize:
+        assert np.allclose(g.sum(1), 1, atol=1e-12)
+        assert np.allclose(g * chosen.sum(1, keepdims=True), chosen, atol=1e-15)
+    else:
+        assert np.array_equal(g, chosen)
+    assert np.all(g > 0) and np.all(g <= 1)
+    # slot order: descending logits; each token's experts are distinct
+    Lc = np.take_along_axis(r["logits"], idx.astype(np.int64), 1)
+    assert np.all(np.diff(Lc, axis=1) <= 0)
+    if cfg.k == 2:
+        assert np.all(idx[:, 0] != idx[:, 1])
+    # the chosen set is a top-k set: nothing outside beats the worst chosen logit
+    rest = r["logits"].copy()
+    np.put_along_axis(rest, idx.astype(np.int64), -np.inf, 1)
+    assert np.all(rest.max(1) <= Lc[:, -1])
+
+
+def test_small_permutation_matches_definition():
+    rng = np.random.default_rng(3)
+    idx = rng.integers(0, 7, size=(40, 2)).astype(np.int32)
+    a = orc.stable_permutation(idx, 7)
+    b = orc.stable_permutation_fast(idx, 7)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_topk_ties_go_to_lowest_index():
+    L = np.array([[1.0, 3.0, 3.0, 3.0, 0.0], [2.0, 2.0, 2.0, 2.0, 2.0]])
+    assert orc.topk_experts(L, 2).tolist() == [[1, 2], [0, 1]]
+    assert orc.topk_experts(L, 1).tolist() == [[1], [0]]
+    assert orc.topk_margin(L, 2).tolist() == [0.0, 0.0]
+    assert orc.topk_margin(np.array([[5.0, 1.0, 3.0]]), 1).tolist() == [2.0]
+    assert orc.topk_margin(np.array([[5.0, 1.0, 3.0]]), 2).tolist() == [2.0]
+
+
+def test_hot_mask_top_h():
+    c = np.array([3, 9, 0, 9, 1, 3], np.int32)
+    assert orc.hot_mask_top_h(c, 0).tolist() == [0, 0, 0, 0, 0, 0]
+    assert orc.hot_mask_top_h(c, 1).tolist() == [0, 1, 0, 0, 0, 0]
+    assert orc.hot_mask_top_h(c, 3).tolist() == [1, 1, 0, 1, 0, 0]
+    assert orc.hot_mask_top_h(c, 6).tolist() == [1] * 6
+    assert orc.hot_mask_top_h(c, 99).tolist() == [1] * 6
+    assert orc.activated_experts(c) == 5
+
+
+# ---------------------------------------------------------------- special cases
+def test_single_expert_is_a_plain_ffn():
+    x, wg, b, W1, W2 = tiny(T=7, E=1, k=1, bias=True)
+    ref = torch.relu(torch.from_numpy(x) @ torch.from_numpy(W1[0]).T) @ torch.from_numpy(W2[0]).T
+    assert np.allclose(run(x, wg, b, W1, W2, 1, False), ref.numpy(), atol=1e-12)
+    assert np.allclose(run(x, wg, b, W1, W2, 1, True), ref.numpy(), atol=1e-12)
+
+
+def test_k_equals_E_is_the_dense_mixture():
+    x, wg, b, W1, W2 = tiny(T=6, E=4, k=4, bias=True)
+    xt = torch.from_numpy(x)
+    p = torch.softmax(xt @ torch.from_numpy(wg).T + torch.from_numpy(b), dim=1)
+    ys = torch.stack([torch.relu(xt @ torch.from_numpy(W1[e]).T) @ torch.from_numpy(W2[e]).T
+                      for e in range(4)], 1)                       # [T,E,d]
+    ref = (p[:, :, None] * ys).sum(1).numpy()
+    assert np.allclose(run(x, wg, b, W1, W2, 4, True), ref, atol=1e-12)
+    assert np.allclose(run(x, wg, b, W1, W2, 4, False), ref, atol=1e-12)
+
+
+def test_identical_experts_and_zero_w2():
+    x, wg, b, W1, W2 = tiny(T=8, E=5, k=2)
+    W1s = np.repeat(W1[:1], 5, 0)
+    W2s = np.repeat(W2[:1], 5, 0)
+    ffn = np.maximum(x @ W1[0].T, 0) @ W2[0].T
+    assert np.allclose(run(x, wg, b, W1s, W2s, 2, True), ffn, atol=1e-12)
+    r = orc.route(x, wg, b, 2, False)
+    assert np.allclose(run(x, wg, b, W1s, W2s, 2, False), r["g"].sum(1, keepdims=True) * ffn,
+                       atol=1e-12)
+    assert np.all(run(x, wg, b, W1, np.zeros_like(W2), 2, True) == 0)
+
+
+def test_relu_is_applied_between_the_layers():
+    # one expert, W1 = -I: every hidden unit is negative for positive inputs -> output 0
+    x = np.abs(np.random.default_rng(0).standard_normal((4, 3))) + 0.1
+    W1 = -np.eye(3)[None]
+    W2 = np.ones((1, 3, 3))
+    assert np.all(run(x, np.zeros((1, 3)), None, W1, W2, 1, False) == 0)
+    assert np.allclose(run(-x, np.zeros((1, 3)), None, W1, W2, 1, False),
+                       np.repeat(x.sum(1, keepdims=True), 3, 1))
+
+
+# ---------------------------------------------------------------- metamorphic
+def test_expert_relabelling_and_token_permutation():
+    x, wg, b, W1, W2 = tiny(T=11, E=6, k=2, bias=True, seed=5)
+    base = run(x, wg, b, W1, W2, 2, True)
+    q = np.random.default_rng(1).permutation(6)
+    assert np.allclose(run(x, wg[q], b[q], W1[q], W2[q], 2, True), base, atol=1e-12)
+    tp = np.random.default_rng(2).permutation(11)
+    assert np.allclose(run(x[tp], wg, b, W1, W2, 2, True), base[tp], atol=1e-12)
+
+
+def test_scaling_and_logit_shift():
+    x, wg, b, W1, W2 = tiny(T=11, E=6, k=2, bias=True, seed=6)
+    base = run(x, wg, b, W1, W2, 2, False)
+    assert np.allclose(run(x, wg, b, W1, 3.5 * W2, 2, False), 3.5 * base, atol=1e-12)
+    assert np.allclose(run(x, wg, b + 2.25, W1, W2, 2, False), base, atol=1e-12)
+    # positive homogeneity of relu: scaling W1 by c > 0 scales the output by c
+    assert np.allclose(run(x, wg, b, 0.5 * W1, W2, 2, False), 0.5 * base, atol=1e-12)
+
+
+def test_mask_algebra():
+    x, wg, b, W1, W2 = tiny(T=13, E=6, k=2, bias=True, seed=8)
+    full = run(x, wg, b, W1, W2, 2, True)
+    m = np.array([1, 0, 1, 1, 0, 0], np.uint8)
+    hot = run(x, wg, b, W1, W2, 2, True, m)
+    cold = run(x, wg, b, W1, W2, 2, True, 1 - m)
+    assert np.allclose(hot + cold, full, atol=1e-12)
+    assert np.all(run(x, wg, b, W1, W2, 2, True, np.zeros(6, np.uint8)) == 0)
+    assert np.array_equal(run(x, wg, b, W1, W2, 2, True, np.ones(6, np.uint8)), full)
+
+
+def test_transposed_operand_would_be_caught():
+    # d != f and non-symmetric weights: using W1 or W2 transposed cannot even multiply,
+    # and a gate indexed [d,E] instead of [E,d] gives another routing -- check the layout
+    x, wg, b, W1, W2 = tiny(T=4, d=3, f=5, E=3, k=1)
+    L = orc.gate_logits(x, wg, None)
+    assert np.allclose(L, np.einsum("td,ed->te", x, wg), atol=1e-14)
+    y = orc.expert_ffn(x, W1[0], W2[0])
+    h = np.maximum(np.einsum("td,fd->tf", x, W1[0]), 0)
+    assert np.allclose(y, np.einsum("tf,df->td", h, W2[0]), atol=1e-14)
+
+
+# ---------------------------------------------------------------- storage rounding
+def test_bf16_rounding_matches_torch_and_oracle():
+    rng = np.random.default_rng(0)
+    a = (rng.standard_normal(200000) * np.exp(rng.uniform(-8, 8, 200000))).astype(np.float32)
+    a[:5] = [0.0, 1.0, 1.00390625, 1.01171875, -3.0]       # includes exact ties
+    ref = torch.from_numpy(a).to(torch.bfloat16)
+    bits = wl.f32_to_bf16_bits(a)
+    assert np.array_equal(bits, ref.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(wl.bf16_bits_to_f32(bits), ref.float().numpy())
+    assert np.array_equal(orc.round_bf16(a.astype(np.float64)), ref.double().numpy())
+    # ties go to even
+    assert orc.round_bf16(np.array([1.00390625, 1.01171875])).tolist() == [1.0, 1.015625]
+
+
+def test_h_rounding_mode_is_close_to_exact():
+    cfg = wl.CONFIGS["switch_base"]
+    W1, W2 = wl.make_expert(cfg, 0)
+    x = wl.make_activations(cfg)[:16]
+    y = orc.expert_ffn(x, W1, W2)
+    yb = orc.expert_ffn(x, W1, W2, "bf16")
+    err = orc.rel_error(yb, y)
+    assert 1e-4 < err.max() < 1e-2
+    assert np.sqrt(np.mean((yb - y) ** 2)) / np.sqrt(np.mean(y ** 2)) < 3e-3
