@@ -1,0 +1,160 @@
+/*
+ * moe.h -- C ABI of the MoE FFN layer forward for AMD MI355X (gfx950).
+ *
+ * The layer is the one the MoNDE paper (arXiv 2405.18832) describes in Section 2.1
+ * and Fig. 1: a gating network scores every (token, expert) pair, each token is
+ * routed to its top-k experts, each expert is linear -> ReLU -> linear, and the
+ * expert outputs are weighted, summed and put back in the original token order.
+ * Section 3.3 splits the experts into a "hot" set (the H experts with the most
+ * tokens) and the rest; every call that runs experts takes an expert mask so the
+ * same library computes the whole layer or only one side's share.
+ *
+ * Notation: T tokens, d = d_model, f = d_ff, E experts, k experts per token,
+ * A = T*k assignments; the flat assignment id is a = t*k + j, slot j = 0 being the
+ * token's best expert.
+ *
+ * General rules for every entry point
+ *  - Every pointer is a DEVICE pointer owned by the caller unless it says "host".
+ *    The library never allocates, frees or keeps a pointer.  Scratch memory comes
+ *    from the caller's workspace `ws` (device, 256-byte aligned, at least
+ *    moe_workspace_bytes(shape) bytes).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls are
+ *    asynchronous on it; they never synchronise and never copy to the host.  Token
+ *    counts stay on the device: kernels read them there.
+ *  - Arguments are validated on the host before anything is launched; on an error
+ *    nothing is written.  Errors are return codes only.
+ *  - Row-major everywhere, last index contiguous.  dtype selects the storage type
+ *    of x, w_gate, W1, W2, x_perm and out; products are accumulated in fp32.
+ *    Gate weights, logits margins and y_perm are always fp32; indices are int32.
+ *  - MOE_BF16 requires d_model % 32 == 0 and d_ff % 32 == 0.  1 <= k <= 8, k <= E,
+ *    E <= 1024, T >= 0.  With T == 0 the per-token buffers are empty and may be NULL:
+ *    moe_route still writes zero counts/offsets (and the hot mask), the other calls are
+ *    no-ops that return MOE_OK.
+ */
+#ifndef MOE_FFN_MI355X_H
+#define MOE_FFN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1,   /* null pointer, bad size, bad enum value            */
+    MOE_ERR_UNSUPPORTED = 2,   /* legal request outside what the kernels cover      */
+    MOE_ERR_WORKSPACE = 3,     /* ws is NULL, misaligned or smaller than required   */
+    MOE_ERR_HIP = 4            /* a HIP call or kernel launch failed                */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef struct {
+    int32_t T, d_model, d_ff, E, k;
+    int32_t dtype;         /* moe_dtype                                              */
+    int32_t renormalize;   /* 0: gate = p_e ; 1: gate = p_e / sum of the chosen k p   */
+    int32_t activation;    /* 0 = ReLU (the only value accepted)                     */
+} moe_shape;
+
+#define MOE_MAX_K 8
+#define MOE_MAX_E 1024
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char* moe_status_string(moe_status s);
+
+/* Bytes of workspace that any entry point may need for this shape (0 on a bad shape). */
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* Bytes of one packed expert-weight tensor (W1 and W2 have the same size). */
+size_t moe_packed_weight_bytes(const moe_shape* shape);
+
+/*
+ * One-time weight preparation (inference weights are static; Section 4.1 runs
+ * pre-trained models).  `which` = 1: src is W1 [E, f, d]; `which` = 2: src is
+ * W2 [E, d, f]; both "out-features x in-features".  dst receives the layout that
+ * moe_expert_ffn / moe_layer_forward read:
+ *   MOE_F32 : a plain copy.
+ *   MOE_BF16: for each expert, 16-row x 32-column fragments, fragment (nb, kb) at
+ *             element offset ((nb * (K/32)) + kb) * 512; inside a fragment the 8
+ *             elements src[16*nb + (l % 16)][32*kb + 8*(l / 16) + 0..7] sit at
+ *             offset 8*l, l = 0..63 -- one 16-byte piece per wavefront lane, in the
+ *             order the MFMA 16x16x32 operand wants them, so a whole fragment is one
+ *             contiguous 1 KiB load.
+ * src and dst must not overlap.
+ */
+moe_status moe_pack_weights(const moe_shape* shape, int32_t which, const void* src,
+                            void* dst, void* stream);
+
+/*
+ * Gating and routing (Section 2.1; Section 3.3 for the histogram and the hot set).
+ *   x [T, d], w_gate [E, d] (row e = gate weights of expert e), gate_bias [E] fp32 or NULL.
+ *   logits = x . w_gate^T + bias (fp32); p = softmax over experts;
+ *   topk_idx [T, k]: experts of the k largest logits, descending, equal logits ordered
+ *                    by lowest expert index;
+ *   topk_w  [T, k]: p of the chosen experts, renormalised over the k if shape->renormalize;
+ *   margin  [T] or NULL: smallest gap between consecutive entries of the k+1 largest logits;
+ *   counts  [E]: assignments per expert; offsets [E+1]: exclusive prefix sum, offsets[E] = A;
+ *   H >= 0 and hot_mask != NULL: hot_mask[e] = 1 for the min(H, E) experts with the largest
+ *                    counts (equal counts ordered by lowest index), else 0.  H < 0: untouched.
+ */
+moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate,
+                     const float* gate_bias, int32_t* topk_idx, float* topk_w, float* margin,
+                     int32_t* counts, int32_t* offsets, int32_t H, uint8_t* hot_mask,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dispatch (Section 2.1 "route each token to the top-k experts"; Section 4.1: drop-less,
+ * padding-less).  Stable counting sort of the A assignments by expert:
+ *   perm [A]: perm[p] = flat assignment id at sorted position p (experts ascending, inside
+ *             an expert ascending flat id);  inv_perm [A]: inv_perm[perm[p]] = p;
+ *   x_perm [A, d] (dtype) or NULL: x_perm[p] = x[perm[p] / k].
+ * `offsets` must be the prefix sums that belong to `topk_idx` (as moe_route writes them).
+ */
+moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* topk_idx,
+                       const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Expert FFNs as one grouped product (Section 2.1: two linear layers with an activation
+ * between; Section 3.1/3.4: C = A x B with a trailing ReLU, then C = A x B).
+ * For every expert e with mask[e] != 0 (mask == NULL: all) and offsets[e+1] > offsets[e]:
+ *   y_perm[offsets[e] .. offsets[e+1]) = relu(X_e . W1_e^T) . W2_e^T        (fp32 rows)
+ * x_perm [A, d] (dtype); w1, w2: packed by moe_pack_weights; y_perm [A, d] fp32.
+ * Rows of masked-out or empty experts are left unwritten.  The hidden activation is
+ * rounded to dtype once between the two products.
+ */
+moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void* w1,
+                          const void* w2, const int32_t* offsets, const uint8_t* mask,
+                          float* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Combine (Section 2.1: outputs are combined and re-organised into the original token order):
+ *   out[t] = sum over j < k with mask[topk_idx[t,j]] != 0 of topk_w[t,j] * y_perm[inv_perm[t*k+j]]
+ * accumulated in fp32, rounded once to dtype.  Masked-out rows of y_perm are not read.
+ * out [T, d] (dtype).
+ */
+moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_t* inv_perm,
+                       const int32_t* topk_idx, const float* topk_w, const uint8_t* mask,
+                       void* out, void* stream);
+
+/*
+ * The whole layer on one stream with no host synchronisation: route -> permute ->
+ * expert FFN -> combine.  mask != NULL: only those experts run and are summed (the
+ * hot share or the cold share of Section 3.3).  mask == NULL and H >= 0: the hot mask
+ * is computed on the device from the token counts (top-H) and used.  mask == NULL and
+ * H < 0: the whole layer.  Gate weights never depend on the mask.
+ * Optional outputs (each may be NULL): topk_idx [T,k], topk_w [T,k], counts [E],
+ * perm [A], hot_mask_out [E] (the mask that was used; all ones for the whole layer).
+ */
+moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* w_gate,
+                             const float* gate_bias, const void* w1, const void* w2,
+                             const uint8_t* mask, int32_t H, void* out,
+                             int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* perm,
+                             uint8_t* hot_mask_out, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_FFN_MI355X_H */

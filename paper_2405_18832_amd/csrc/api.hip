@@ -1,0 +1,166 @@
+// C ABI of the MoE FFN library: argument validation on the host, then asynchronous kernel
+// launches on the caller's stream.  No entry point allocates, synchronises or copies to the host.
+#include "common.hpp"
+
+using namespace moe;
+
+namespace {
+
+moe_status check_shape(const moe_shape* s) {
+    if (s == nullptr) return MOE_ERR_INVALID_ARG;
+    if (s->T < 0 || s->d_model <= 0 || s->d_ff <= 0 || s->E <= 0 || s->k <= 0) return MOE_ERR_INVALID_ARG;
+    if (s->k > s->E) return MOE_ERR_INVALID_ARG;
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
+    if (s->renormalize != 0 && s->renormalize != 1) return MOE_ERR_INVALID_ARG;
+    if (s->activation != 0) return MOE_ERR_UNSUPPORTED;
+    if (s->k > MOE_MAX_K || s->E > MOE_MAX_E) return MOE_ERR_UNSUPPORTED;
+    if (s->dtype == MOE_BF16 && (s->d_model % 32 != 0 || s->d_ff % 32 != 0)) return MOE_ERR_UNSUPPORTED;
+    // int32 indexing of assignments and of rows
+    const long long A = static_cast<long long>(s->T) * s->k;
+    if (A > 0x3fffffffLL) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+moe_status check_ws(const moe_shape* s, const void* ws, size_t ws_bytes) {
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return MOE_ERR_WORKSPACE;
+    if (ws_bytes < ws_layout(*s).total) return MOE_ERR_WORKSPACE;
+    return MOE_OK;
+}
+
+inline moe_status from_hip(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+template <typename T> inline T* at(void* ws, size_t off) {
+    return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(moe_status s) {
+    switch (s) {
+        case MOE_OK: return "MOE_OK";
+        case MOE_ERR_INVALID_ARG: return "MOE_ERR_INVALID_ARG";
+        case MOE_ERR_UNSUPPORTED: return "MOE_ERR_UNSUPPORTED";
+        case MOE_ERR_WORKSPACE: return "MOE_ERR_WORKSPACE";
+        case MOE_ERR_HIP: return "MOE_ERR_HIP";
+    }
+    return "MOE_ERR_UNKNOWN";
+}
+
+size_t moe_workspace_bytes(const moe_shape* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return ws_layout(*shape).total;
+}
+
+size_t moe_packed_weight_bytes(const moe_shape* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return static_cast<size_t>(shape->E) * shape->d_model * shape->d_ff * elem_size(shape->dtype);
+}
+
+moe_status moe_pack_weights(const moe_shape* shape, int32_t which, const void* src, void* dst, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((which != 1 && which != 2) || src == nullptr || dst == nullptr || src == dst) return MOE_ERR_INVALID_ARG;
+    return from_hip(launch_pack(*shape, which, src, dst, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, const float* gate_bias,
+                     int32_t* topk_idx, float* topk_w, float* margin, int32_t* counts, int32_t* offsets,
+                     int32_t H, uint8_t* hot_mask, void* ws, size_t ws_bytes, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (counts == nullptr || offsets == nullptr) return MOE_ERR_INVALID_ARG;
+    if (H >= 0 && hot_mask == nullptr) return MOE_ERR_INVALID_ARG;
+    // with no tokens the per-token buffers are empty and may be NULL
+    if (shape->T > 0 && (x == nullptr || w_gate == nullptr || topk_idx == nullptr || topk_w == nullptr))
+        return MOE_ERR_INVALID_ARG;
+    st = check_ws(shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    const WsLayout L = ws_layout(*shape);
+    return from_hip(launch_route(*shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, offsets, H,
+                                 hot_mask, at<float>(ws, L.logits), static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* topk_idx, const int32_t* offsets,
+                       int32_t* perm, int32_t* inv_perm, void* x_perm, void* ws, size_t ws_bytes, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    if (topk_idx == nullptr || offsets == nullptr || perm == nullptr || inv_perm == nullptr)
+        return MOE_ERR_INVALID_ARG;
+    if (x_perm != nullptr && x == nullptr) return MOE_ERR_INVALID_ARG;
+    st = check_ws(shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    const WsLayout L = ws_layout(*shape);
+    return from_hip(launch_permute(*shape, x, topk_idx, offsets, perm, inv_perm, x_perm, at<int32_t>(ws, L.hist),
+                                   static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void* w1, const void* w2,
+                          const int32_t* offsets, const uint8_t* mask, float* y_perm, void* ws, size_t ws_bytes,
+                          void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    if (x_perm == nullptr || w1 == nullptr || w2 == nullptr || offsets == nullptr || y_perm == nullptr)
+        return MOE_ERR_INVALID_ARG;
+    st = check_ws(shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    const WsLayout L = ws_layout(*shape);
+    return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, offsets, mask, y_perm, at<void>(ws, L.h),
+                                      at<Tile>(ws, L.tiles), at<int32_t>(ws, L.ntiles),
+                                      static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_t* inv_perm,
+                       const int32_t* topk_idx, const float* topk_w, const uint8_t* mask, void* out, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->T == 0) return MOE_OK;
+    if (y_perm == nullptr || inv_perm == nullptr || topk_idx == nullptr || topk_w == nullptr || out == nullptr)
+        return MOE_ERR_INVALID_ARG;
+    return from_hip(launch_combine(*shape, y_perm, inv_perm, topk_idx, topk_w, mask, out,
+                                   static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* w_gate, const float* gate_bias,
+                             const void* w1, const void* w2, const uint8_t* mask, int32_t H, void* out,
+                             int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* perm,
+                             uint8_t* hot_mask_out, void* ws, size_t ws_bytes, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->T > 0 && (x == nullptr || w_gate == nullptr || w1 == nullptr || w2 == nullptr || out == nullptr))
+        return MOE_ERR_INVALID_ARG;
+    st = check_ws(shape, ws, ws_bytes);
+    if (st != MOE_OK) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const WsLayout L = ws_layout(*shape);
+    int32_t* idx = topk_idx ? topk_idx : at<int32_t>(ws, L.idx);
+    float* gate = topk_w ? topk_w : at<float>(ws, L.gate);
+    int32_t* cnt = counts ? counts : at<int32_t>(ws, L.counts);
+    int32_t* prm = perm ? perm : at<int32_t>(ws, L.perm);
+    int32_t* offsets = at<int32_t>(ws, L.offsets);
+    int32_t* inv = at<int32_t>(ws, L.inv_perm);
+    uint8_t* own_mask = at<uint8_t>(ws, L.mask);
+    const bool derive = (mask == nullptr && H >= 0);
+    const uint8_t* used = mask ? mask : (derive ? own_mask : nullptr);
+
+    hipError_t e = launch_route(*shape, x, w_gate, gate_bias, idx, gate, nullptr, cnt, offsets,
+                                derive ? H : -1, derive ? own_mask : nullptr, at<float>(ws, L.logits), hs);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    if (hot_mask_out != nullptr) {
+        e = launch_mask_out(used, hot_mask_out, shape->E, hs);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+    }
+    if (shape->T == 0) return MOE_OK;
+    e = launch_permute(*shape, x, idx, offsets, prm, inv, at<void>(ws, L.x_perm), at<int32_t>(ws, L.hist), hs);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    e = launch_expert_ffn(*shape, at<void>(ws, L.x_perm), w1, w2, offsets, used, at<float>(ws, L.y_perm),
+                          at<void>(ws, L.h), at<Tile>(ws, L.tiles), at<int32_t>(ws, L.ntiles), hs);
+    if (e != hipSuccess) return MOE_ERR_HIP;
+    e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
+    return from_hip(e);
+}
+
+}  // extern "C"

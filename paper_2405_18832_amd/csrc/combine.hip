@@ -1,0 +1,80 @@
+// Combine: weight each token's expert outputs by its gate weights, sum them and store the
+// result at the token's original position (paper Section 2.1: outputs are combined and
+// re-organised into the original order of the input tokens).  With an expert mask only the
+// masked-in experts contribute (Section 3.3: the share of one side of the hot/cold split).
+#include "common.hpp"
+
+namespace moe {
+
+// One wavefront per token; a lane owns 4 consecutive columns per 256-column step, reads them
+// as one 16-byte piece from each of the token's k rows of y_perm and keeps the sum in fp32.
+template <typename ST, int VEC>
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y_perm,
+                                                      const int32_t* __restrict__ inv_perm,
+                                                      const int32_t* __restrict__ idx,
+                                                      const float* __restrict__ gate,
+                                                      const uint8_t* __restrict__ mask,
+                                                      ST* __restrict__ out, int T, int d, int k, int E,
+                                                      int A) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= T) return;
+    const float* rows[MOE_MAX_K];
+    float w[MOE_MAX_K];
+    int n = 0;
+    for (int j = 0; j < k; ++j) {
+        const int a = t * k + j;
+        const int e = idx[a];
+        const int p = inv_perm[a];
+        const bool on = (e >= 0 && e < E && p >= 0 && p < A) && (mask == nullptr || mask[e] != 0);
+        if (on) {
+            rows[n] = y_perm + static_cast<size_t>(p) * d;
+            w[n] = gate[a];
+            ++n;
+        }
+    }
+    ST* o = out + static_cast<size_t>(t) * d;
+    for (int c = lane * VEC; c < d; c += 64 * VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+        for (int j = 0; j < n; ++j) {
+            if (VEC == 4) {
+                const float4 v = *reinterpret_cast<const float4*>(rows[j] + c);
+                acc[0] = fmaf(w[j], v.x, acc[0]);
+                acc[1] = fmaf(w[j], v.y, acc[1]);
+                acc[2] = fmaf(w[j], v.z, acc[2]);
+                acc[3] = fmaf(w[j], v.w, acc[3]);
+            } else {
+                acc[0] = fmaf(w[j], rows[j][c], acc[0]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) Storage<ST>::store(o + c + i, acc[i]);
+    }
+}
+
+hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t* inv_perm,
+                          const int32_t* idx, const float* gate, const uint8_t* mask, void* out,
+                          hipStream_t st) {
+    const int T = s.T, d = s.d_model, k = s.k, E = s.E, A = s.T * s.k;
+    const dim3 grid((T + 3) / 4), block(256);
+    if (s.dtype == MOE_BF16) {
+        if (d % 4 == 0)
+            hipLaunchKernelGGL((combine_kernel<uint16_t, 4>), grid, block, 0, st, y_perm, inv_perm, idx, gate,
+                               mask, static_cast<uint16_t*>(out), T, d, k, E, A);
+        else
+            hipLaunchKernelGGL((combine_kernel<uint16_t, 1>), grid, block, 0, st, y_perm, inv_perm, idx, gate,
+                               mask, static_cast<uint16_t*>(out), T, d, k, E, A);
+    } else {
+        if (d % 4 == 0)
+            hipLaunchKernelGGL((combine_kernel<float, 4>), grid, block, 0, st, y_perm, inv_perm, idx, gate, mask,
+                               static_cast<float*>(out), T, d, k, E, A);
+        else
+            hipLaunchKernelGGL((combine_kernel<float, 1>), grid, block, 0, st, y_perm, inv_perm, idx, gate, mask,
+                               static_cast<float*>(out), T, d, k, E, A);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,120 @@
+// Shared declarations of the MoE FFN library for gfx950: storage helpers, the
+// workspace layout and the internal launch functions that the C ABI composes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+// ---- bf16 storage <-> fp32 ------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+template <typename ST> struct Storage;
+template <> struct Storage<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Storage<uint16_t> {
+    static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- expert tiles: the unit the FFN kernels schedule ------------------------
+// A tile is up to `tile_rows` consecutive rows of one expert's segment of x_perm.
+struct Tile {
+    int32_t expert;
+    int32_t row0;    // first row in x_perm / h / y_perm
+    int32_t rows;    // 1 .. tile_rows
+    int32_t pad;
+};
+
+// ---- workspace ----------------------------------------------------------------
+struct WsLayout {
+    size_t logits;     // float [T, E]
+    size_t hist;       // int32 [ceil(A/256), E]
+    size_t ntiles;     // int32 [64]  (element 0 used)
+    size_t tiles;      // Tile [A/16 + E + 1]
+    size_t h;          // dtype [A, f]
+    size_t idx;        // int32 [A]         -- the rest is used by moe_layer_forward only
+    size_t gate;       // float [A]
+    size_t counts;     // int32 [E]
+    size_t offsets;    // int32 [E + 1]
+    size_t perm;       // int32 [A]
+    size_t inv_perm;   // int32 [A]
+    size_t mask;       // uint8 [E]
+    size_t x_perm;     // dtype [A, d]
+    size_t y_perm;     // float [A, d]
+    size_t total;
+};
+
+constexpr int kPermChunk = 256;   // assignments per counting-sort chunk (one wavefront)
+
+inline size_t elem_size(int32_t dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+inline WsLayout ws_layout(const moe_shape& s) {
+    WsLayout L{};
+    const size_t A = static_cast<size_t>(s.T) * s.k, E = s.E, es = elem_size(s.dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off += (bytes + 255) & ~static_cast<size_t>(255);
+        return at;
+    };
+    L.logits = take(static_cast<size_t>(s.T) * E * 4);
+    L.hist = take(((A + kPermChunk - 1) / kPermChunk) * E * 4);
+    L.ntiles = take(64 * 4);
+    L.tiles = take((A / 16 + E + 1) * sizeof(Tile));
+    L.h = take(A * s.d_ff * es);
+    L.idx = take(A * 4);
+    L.gate = take(A * 4);
+    L.counts = take(E * 4);
+    L.offsets = take((E + 1) * 4);
+    L.perm = take(A * 4);
+    L.inv_perm = take(A * 4);
+    L.mask = take(E);
+    L.x_perm = take(A * s.d_model * es);
+    L.y_perm = take(A * s.d_model * 4);
+    L.total = off;
+    return L;
+}
+
+// ---- internal launchers (all asynchronous on `st`; return hipSuccess or the launch error)
+hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                        int32_t* idx, float* gate, float* margin, int32_t* counts,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, float* logits_ws,
+                        hipStream_t st);
+hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
+                          const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
+                          int32_t* hist_ws, hipStream_t st);
+hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
+                             const int32_t* offsets, const uint8_t* mask, float* y_perm,
+                             void* h_ws, Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st);
+hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t* inv_perm,
+                          const int32_t* idx, const float* gate, const uint8_t* mask, void* out,
+                          hipStream_t st);
+hipError_t launch_pack(const moe_shape& s, int which, const void* src, void* dst, hipStream_t st);
+hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hipStream_t st);
+
+// number of compute units of the current device (cached)
+int device_cu_count();
+
+}  // namespace moe

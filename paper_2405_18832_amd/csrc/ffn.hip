@@ -1,0 +1,362 @@
+// Expert FFNs as a grouped product over variable token counts:
+//   y_perm[rows of e] = relu(x_perm[rows of e] . W1_e^T) . W2_e^T        for every active expert e
+// (paper Section 2.1: an expert is two linear layers with an activation between; Sections 3.1
+// and 3.4: each is C = A x B, the first with a trailing ReLU).  The paper's observation that
+// most experts receive very few tokens, so that their cost is reading their parameters
+// (Section 2.2), is what shapes the kernel below: it streams every active expert's weights
+// exactly once at full memory bandwidth while the few token rows ride along as the other MFMA
+// operand.
+#include "common.hpp"
+
+namespace moe {
+
+// ---------------------------------------------------------------------------
+// weight packing: [E][N][K] row-major  ->  [E][N/16][K/32] fragments of 64 lanes x 8 elements.
+// One thread per 16-byte piece of the destination.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict__ src,
+                                                        uint4* __restrict__ dst, int N, int K,
+                                                        size_t total) {
+    const size_t c = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (c >= total) return;
+    const size_t per_expert = static_cast<size_t>(N) * K / 8;
+    const size_t e = c / per_expert, ce = c % per_expert;
+    const int kblk = K / 32;
+    const size_t frag = ce / 64;
+    const int l = static_cast<int>(ce % 64);
+    const int nb = static_cast<int>(frag / kblk), kb = static_cast<int>(frag % kblk);
+    const int n = nb * 16 + (l & 15), kk = kb * 32 + (l >> 4) * 8;
+    dst[c] = src[(e * N + n) * (K / 8) + kk / 8];
+}
+
+__global__ __launch_bounds__(256) void copy_u32_kernel(const uint32_t* __restrict__ src,
+                                                       uint32_t* __restrict__ dst, size_t total) {
+    const size_t c = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (c < total) dst[c] = src[c];
+}
+
+hipError_t launch_pack(const moe_shape& s, int which, const void* src, void* dst, hipStream_t st) {
+    const int N = which == 1 ? s.d_ff : s.d_model, K = which == 1 ? s.d_model : s.d_ff;
+    if (s.dtype == MOE_BF16) {
+        const size_t total = static_cast<size_t>(s.E) * N * K / 8;
+        hipLaunchKernelGGL(pack_bf16_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
+                           st, static_cast<const uint4*>(src), static_cast<uint4*>(dst), N, K, total);
+    } else {
+        const size_t total = static_cast<size_t>(s.E) * N * K;
+        hipLaunchKernelGGL(copy_u32_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
+                           st, static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst), total);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// tile list: every active expert's row segment cut into tiles of `tile_rows` rows.
+// One block, one thread per expert, exclusive scan of the tile counts in LDS.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets,
+                                                           const uint8_t* __restrict__ mask,
+                                                           Tile* __restrict__ tiles,
+                                                           int32_t* __restrict__ ntiles, int E, int A,
+                                                           int tile_rows) {
+    __shared__ int32_t scan[MOE_MAX_E];
+    const int e = threadIdx.x;
+    int row0 = 0, m = 0;
+    if (e < E && (mask == nullptr || mask[e] != 0)) {
+        row0 = offsets[e];
+        m = offsets[e + 1] - row0;
+        if (row0 < 0 || m < 0 || row0 + m > A) m = 0;   // offsets that are not prefix sums: run nothing
+    }
+    const int nt = (m + tile_rows - 1) / tile_rows;
+    scan[e] = nt;
+    __syncthreads();
+    for (int s = 1; s < MOE_MAX_E; s <<= 1) {
+        const int add = (e >= s) ? scan[e - s] : 0;
+        __syncthreads();
+        scan[e] += add;
+        __syncthreads();
+    }
+    const int base = scan[e] - nt;
+    for (int i = 0; i < nt; ++i) {
+        Tile t;
+        t.expert = e;
+        t.row0 = row0 + i * tile_rows;
+        t.rows = min(tile_rows, m - i * tile_rows);
+        t.pad = 0;
+        tiles[base + i] = t;
+    }
+    if (e == MOE_MAX_E - 1) ntiles[0] = scan[e];
+}
+
+// ---------------------------------------------------------------------------
+// bf16 weight-streaming product.
+//
+//   out[row, n] = sum_k act[row, k] * W_e[n, k]          (FIRST: relu, rounded to bf16)
+//
+// MFMA 16x16x32: the A operand is a packed 16(n) x 32(k) weight fragment -- one contiguous
+// 1 KiB load per wavefront, 16 bytes per lane, straight from HBM into registers -- and the B
+// operand is 16 token rows x 32 k of the activations (L2/L1 hits; every wave of a block reads
+// the same rows).  A wavefront owns 4 n-blocks (64 output columns) x up to TFMAX*16 token rows
+// over one k-slice; the KSPLIT wavefronts that share an output tile add their partial sums in
+// LDS in a fixed order.  Blocks are persistent and stride over (tile, n-group) units, whose
+// number is only known on the device.  PF k-steps of loads are kept in flight per wavefront.
+// ---------------------------------------------------------------------------
+template <int TFMAX, int KSPLIT, int PF, bool FIRST>
+__global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
+                                                         const uint16_t* __restrict__ wpk,
+                                                         void* __restrict__ outp,
+                                                         const Tile* __restrict__ tiles,
+                                                         const int32_t* __restrict__ ntiles_p, int N,
+                                                         int K) {
+    constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
+    __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int ks = wave % KSPLIT, ngs = wave / KSPLIT;
+    const int nblk = N >> 4, kblk = K >> 5;
+    const int ngroups = (nblk + 3) >> 2;
+    const int ngchunks = (ngroups + NGB - 1) / NGB;
+    const int kb_per = (kblk + KSPLIT - 1) / KSPLIT;
+    const int kb0 = min(kblk, ks * kb_per), kb1 = min(kblk, kb0 + kb_per);
+    const int nbu = ntiles_p[0] * ngchunks;
+
+    for (int bu = blockIdx.x; bu < nbu; bu += gridDim.x) {
+        const Tile tl = tiles[bu / ngchunks];
+        const int ng = (bu % ngchunks) * NGB + ngs;
+        const bool active = ng < ngroups;                 // wave-uniform
+        const int tfc = (tl.rows + 15) >> 4;              // token fragments in use, 1..TFMAX
+        f32x4 acc[4][TFMAX];
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+            for (int tf = 0; tf < TFMAX; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        if (active) {
+            const uint16_t* wp[4];
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf) {
+                const int nb = min(ng * 4 + nf, nblk - 1);
+                wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
+            }
+            const uint16_t* ap[TFMAX];
+#pragma unroll
+            for (int tf = 0; tf < TFMAX; ++tf) {
+                const int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+                ap[tf] = act + static_cast<size_t>(row) * K + g * 8;
+            }
+            bf16x8 a[PF][4], b[PF][TFMAX];
+            auto issue = [&](int slot, int kb) {
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+                    a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
+#pragma unroll
+                for (int tf = 0; tf < TFMAX; ++tf)
+                    if (tf < tfc) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * 32);
+            };
+            auto fma = [&](int slot) {
+#pragma unroll
+                for (int tf = 0; tf < TFMAX; ++tf)
+                    if (tf < tfc) {
+#pragma unroll
+                        for (int nf = 0; nf < 4; ++nf)
+                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[slot][tf],
+                                                                                  acc[nf][tf], 0, 0, 0);
+                    }
+            };
+#pragma unroll
+            for (int p = 0; p < PF; ++p)
+                if (kb0 + p < kb1) issue(p, kb0 + p);
+            int kb = kb0;
+            for (; kb + 2 * PF <= kb1; kb += PF) {        // steady state: no bounds checks
+#pragma unroll
+                for (int p = 0; p < PF; ++p) {
+                    fma(p);
+                    issue(p, kb + p + PF);
+                }
+            }
+            for (; kb < kb1; kb += PF) {                  // drain
+#pragma unroll
+                for (int p = 0; p < PF; ++p)
+                    if (kb + p < kb1) {
+                        fma(p);
+                        if (kb + p + PF < kb1) issue(p, kb + p + PF);
+                    }
+            }
+        }
+
+        if (KSPLIT > 1) {
+            if (active && ks > 0) {
+                f32x4* dst = red + (static_cast<size_t>((ks - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+                    for (int tf = 0; tf < TFMAX; ++tf)
+                        if (tf < tfc) dst[(nf * TFMAX + tf) * 64] = acc[nf][tf];
+            }
+            __syncthreads();
+            if (active && ks == 0) {
+#pragma unroll
+                for (int s = 1; s < KSPLIT; ++s) {
+                    const f32x4* src = red + (static_cast<size_t>((s - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+#pragma unroll
+                    for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+                        for (int tf = 0; tf < TFMAX; ++tf)
+                            if (tf < tfc) acc[nf][tf] += src[(nf * TFMAX + tf) * 64];
+                }
+            }
+        }
+        if (active && ks == 0) {
+#pragma unroll
+            for (int tf = 0; tf < TFMAX; ++tf) {
+                const int lr = tf * 16 + r;
+                if (lr >= tl.rows) continue;
+                const size_t rowoff = static_cast<size_t>(tl.row0 + lr) * N;
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf) {
+                    const int nb = ng * 4 + nf;
+                    if (nb >= nblk) continue;
+                    const int n = nb * 16 + g * 4;
+                    const f32x4 v = acc[nf][tf];
+                    if (FIRST) {
+                        uint2 pk;
+                        pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
+                        pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + rowoff + n) = pk;
+                    } else {
+                        *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + rowoff + n) = v;
+                    }
+                }
+            }
+        }
+        if (KSPLIT > 1) __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// fp32 storage: plain FMA kernel (small layers only).  Tiles of 16 rows; a thread owns one
+// output column of a tile and walks the rows.
+// ---------------------------------------------------------------------------
+template <bool FIRST>
+__global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ act,
+                                                      const float* __restrict__ w,
+                                                      float* __restrict__ outp,
+                                                      const Tile* __restrict__ tiles,
+                                                      const int32_t* __restrict__ ntiles_p, int N, int K) {
+    const int nchunks = (N + 255) / 256;
+    const int nbu = ntiles_p[0] * nchunks;
+    for (int bu = blockIdx.x; bu < nbu; bu += gridDim.x) {
+        const Tile tl = tiles[bu / nchunks];
+        const int n = (bu % nchunks) * 256 + threadIdx.x;
+        if (n >= N) continue;
+        const float* wr = w + (static_cast<size_t>(tl.expert) * N + n) * K;
+        for (int i = 0; i < tl.rows; ++i) {
+            const float* ar = act + static_cast<size_t>(tl.row0 + i) * K;
+            float s = 0.f;
+            for (int c = 0; c < K; ++c) s = fmaf(ar[c], wr[c], s);
+            outp[static_cast<size_t>(tl.row0 + i) * N + n] = FIRST ? fmaxf(s, 0.f) : s;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+int device_cu_count() {
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+template <int TFMAX, int KSPLIT, int PF, bool FIRST>
+static hipError_t launch_stream(const uint16_t* act, const uint16_t* wpk, void* outp, const Tile* tiles,
+                                const int32_t* ntiles, int N, int K, long max_units, hipStream_t st) {
+    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, PF, FIRST>;
+    static int per_cu = 0;
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 256, 0) != hipSuccess || n <= 0) n = 1;
+        per_cu = n;
+    }
+    long grid = static_cast<long>(device_cu_count()) * per_cu;
+    if (grid > max_units) grid = max_units;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, wpk, outp, tiles, ntiles, N, K);
+    return hipGetLastError();
+}
+
+template <int TFMAX, int PF, bool FIRST>
+static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const uint16_t* wpk, void* outp,
+                                  const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
+                                  hipStream_t st) {
+    const long ngroups = (N / 16 + 3) / 4;
+    if (ksplit == 4)
+        return launch_stream<TFMAX, 4, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
+    if (ksplit == 2)
+        return launch_stream<TFMAX, 2, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ((ngroups + 1) / 2), st);
+    return launch_stream<TFMAX, 1, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ((ngroups + 3) / 4), st);
+}
+
+// k-steps of 32 per wavefront: split K over up to 4 wavefronts while each keeps >= 24 steps
+static int pick_ksplit(int K) {
+    const int steps = K / 32;
+    if (steps >= 96) return 4;
+    if (steps >= 48) return 2;
+    return 1;
+}
+
+hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
+                             const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
+                             Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st) {
+    const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
+    // an expert holds at most T rows (a token picks an expert at most once)
+    int tfmax = 4;
+    if (s.dtype == MOE_BF16) tfmax = s.T <= 16 ? 1 : (s.T <= 32 ? 2 : 4);
+    const int tile_rows = s.dtype == MOE_BF16 ? 16 * tfmax : 16;
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, tiles_ws, ntiles_ws, E, A,
+                       tile_rows);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const long max_tiles = A / tile_rows + (E < A ? E : A);
+
+    if (s.dtype == MOE_F32) {
+        const long g1 = max_tiles * ((f + 255) / 256), g2 = max_tiles * ((d + 255) / 256);
+        const long cap = static_cast<long>(device_cu_count()) * 8;
+        hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(static_cast<unsigned>(g1 < cap ? g1 : cap)), dim3(256), 0, st,
+                           static_cast<const float*>(x_perm), static_cast<const float*>(w1),
+                           static_cast<float*>(h_ws), tiles_ws, ntiles_ws, f, d);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
+                           static_cast<const float*>(h_ws), static_cast<const float*>(w2), y_perm, tiles_ws,
+                           ntiles_ws, d, f);
+        return hipGetLastError();
+    }
+
+    const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
+    const uint16_t* p1 = static_cast<const uint16_t*>(w1);
+    const uint16_t* p2 = static_cast<const uint16_t*>(w2);
+    uint16_t* h = static_cast<uint16_t*>(h_ws);
+    const int ks1 = pick_ksplit(d), ks2 = pick_ksplit(f);
+    switch (tfmax) {
+        case 1:
+            err = launch_stream_k<1, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
+            if (err != hipSuccess) return err;
+            return launch_stream_k<1, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
+        case 2:
+            err = launch_stream_k<2, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
+            if (err != hipSuccess) return err;
+            return launch_stream_k<2, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
+        default:
+            err = launch_stream_k<4, 3, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
+            if (err != hipSuccess) return err;
+            return launch_stream_k<4, 3, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
+    }
+}
+
+}  // namespace moe

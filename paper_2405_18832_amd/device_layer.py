@@ -1,0 +1,116 @@
+"""Device-side buffers of one MoE FFN layer: allocation, host->HBM upload, one-time weight
+packing, and calls into the C ABI.  No arithmetic happens here.
+
+Used by the tests, the smoke check and the bench.  Inputs arrive as numpy float32 arrays whose
+values are already representable in the layer's storage dtype.
+"""
+from __future__ import annotations
+
+from concurrent.futures import ThreadPoolExecutor
+from typing import Callable, Iterable, Optional
+
+import numpy as np
+import torch
+
+from . import (make_shape, moe_combine, moe_expert_ffn, moe_layer_forward, moe_pack_weights,
+               moe_permute, moe_route, moe_workspace_bytes)
+
+
+def torch_dtype(dtype: str):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
+    """Exact conversion: the values are representable in `dtype` already."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch_dtype(dtype)).to(device)
+
+
+class DeviceLayer:
+    def __init__(self, cfg, x: np.ndarray, w_gate: np.ndarray, b_gate: Optional[np.ndarray],
+                 expert: Callable[[int], tuple], experts: Optional[Iterable[int]] = None,
+                 device: str = "cuda:0", workers: int = 8):
+        """cfg needs T, d_model, d_ff, E, k, dtype ("f32"|"bf16"), renormalize.
+        `expert(e)` returns (W1_e [d_ff, d_model], W2_e [d_model, d_ff]).  If `experts` is
+        given, only those experts get their real weights; the others are filled with
+        device-generated normal noise of the same scale (used when only a known subset can
+        receive tokens and generating all weights on the host would take minutes)."""
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.shape = make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.dtype, cfg.renormalize)
+        td = torch_dtype(cfg.dtype)
+        self.dtype = td
+        T, d, f, E, k = cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k
+        A = T * k
+        dev = self.device
+        self.x = to_device(x, cfg.dtype, dev)
+        self.w_gate = to_device(w_gate, cfg.dtype, dev)
+        self.b_gate = None if b_gate is None else torch.from_numpy(
+            np.ascontiguousarray(b_gate, dtype=np.float32)).to(dev)
+
+        want = list(range(E)) if experts is None else sorted(set(int(e) for e in experts))
+        w1_plain = torch.empty((E, f, d), dtype=td, device=dev)
+        w2_plain = torch.empty((E, d, f), dtype=td, device=dev)
+        if len(want) < E:
+            gen = torch.Generator(device=dev).manual_seed(12345)
+            for e in range(E):      # per expert: keeps the fp32 temporary small
+                w1_plain[e] = (torch.randn((f, d), device=dev, generator=gen) / d ** 0.5).to(td)
+                w2_plain[e] = (torch.randn((d, f), device=dev, generator=gen) / f ** 0.5).to(td)
+        with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
+            for i in range(0, len(want), workers):
+                es = want[i:i + workers]
+                for e, (w1, w2) in zip(es, pool.map(expert, es)):
+                    w1_plain[e].copy_(torch.from_numpy(w1).to(td))
+                    w2_plain[e].copy_(torch.from_numpy(w2).to(td))
+        self.w1 = torch.empty_like(w1_plain)
+        self.w2 = torch.empty_like(w2_plain)
+        moe_pack_weights(self.shape, 1, w1_plain, self.w1)
+        moe_pack_weights(self.shape, 2, w2_plain, self.w2)
+        torch.cuda.synchronize(dev)
+        del w1_plain, w2_plain
+
+        self.ws = torch.empty(max(256, moe_workspace_bytes(self.shape)), dtype=torch.uint8, device=dev)
+        i32, f32 = torch.int32, torch.float32
+        self.topk_idx = torch.empty((T, k), dtype=i32, device=dev)
+        self.topk_w = torch.empty((T, k), dtype=f32, device=dev)
+        self.margin = torch.empty((T,), dtype=f32, device=dev)
+        self.counts = torch.empty((E,), dtype=i32, device=dev)
+        self.offsets = torch.empty((E + 1,), dtype=i32, device=dev)
+        self.hot_mask = torch.empty((E,), dtype=torch.uint8, device=dev)
+        self.perm = torch.empty((A,), dtype=i32, device=dev)
+        self.inv_perm = torch.empty((A,), dtype=i32, device=dev)
+        self.x_perm = torch.empty((A, d), dtype=td, device=dev)
+        self.y_perm = torch.empty((A, d), dtype=f32, device=dev)
+        self.out = torch.empty((T, d), dtype=td, device=dev)
+
+    # ---- the five entry points on this layer's buffers --------------------------------
+    def route(self, H: int = -1):
+        moe_route(self.shape, self.x, self.w_gate, self.b_gate, self.topk_idx, self.topk_w, self.margin,
+                  self.counts, self.offsets, H, self.hot_mask if H >= 0 else None, self.ws)
+
+    def permute(self, topk_idx=None, offsets=None):
+        moe_permute(self.shape, self.x, self.topk_idx if topk_idx is None else topk_idx,
+                    self.offsets if offsets is None else offsets, self.perm, self.inv_perm, self.x_perm,
+                    self.ws)
+
+    def expert_ffn(self, mask=None, x_perm=None, offsets=None):
+        moe_expert_ffn(self.shape, self.x_perm if x_perm is None else x_perm, self.w1, self.w2,
+                       self.offsets if offsets is None else offsets, mask, self.y_perm, self.ws)
+
+    def combine(self, mask=None, y_perm=None, inv_perm=None, topk_idx=None, topk_w=None):
+        moe_combine(self.shape, self.y_perm if y_perm is None else y_perm,
+                    self.inv_perm if inv_perm is None else inv_perm,
+                    self.topk_idx if topk_idx is None else topk_idx,
+                    self.topk_w if topk_w is None else topk_w, mask, self.out)
+
+    def forward(self, mask=None, H: int = -1, debug: bool = False):
+        if debug:
+            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, self.w1, self.w2, mask, H,
+                              self.out, self.topk_idx, self.topk_w, self.counts, self.perm, self.hot_mask,
+                              self.ws)
+        else:
+            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, self.w1, self.w2, mask, H,
+                              self.out, ws=self.ws)
+        return self.out
+
+    def out_numpy(self) -> np.ndarray:
+        return self.out.float().cpu().numpy()

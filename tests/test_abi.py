@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, rejects bad arguments before launching anything, and sizes its workspace sanely."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_18832_amd as moe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    names = declared_functions()
+    assert sorted(moe.EXPORTS) == names
+    for n in ["moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
+        assert n in names and callable(getattr(moe, n))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = moe.load()
+    for n in declared_functions():
+        assert getattr(lib, n) is not None
+    assert moe.status_string(0) == "MOE_OK"
+    assert moe.status_string(3) == "MOE_ERR_WORKSPACE"
+
+
+def shape(**kw):
+    base = dict(T=64, d_model=64, d_ff=256, E=8, k=2, dtype="bf16", renormalize=True)
+    base.update(kw)
+    return moe.make_shape(**base)
+
+
+def test_workspace_size():
+    s = shape()
+    n = moe.moe_workspace_bytes(s)
+    A = 64 * 2
+    assert n >= A * 256 * 2 + A * 64 * 4 + A * 64 * 2      # h + y_perm + x_perm at least
+    assert n % 256 == 0
+    assert moe.moe_workspace_bytes(shape(T=128)) > n
+    assert moe.moe_packed_weight_bytes(s) == 8 * 64 * 256 * 2
+    assert moe.moe_packed_weight_bytes(shape(dtype="f32")) == 8 * 64 * 256 * 4
+    assert moe.moe_workspace_bytes(shape(k=9)) == 0         # bad shape -> 0
+
+
+FAKE = 0x1000      # a non-null, 256-aligned address that is never dereferenced on these paths
+
+
+def route_status(s, x=FAKE, wg=FAKE, idx=FAKE, w=FAKE, counts=FAKE, offsets=FAKE, H=-1, hot=None,
+                 ws=FAKE, ws_bytes=None):
+    lib = moe.load()
+    if ws_bytes is None:
+        ws_bytes = max(256, moe.moe_workspace_bytes(s))
+    return lib.moe_route(ctypes.byref(s), x, wg, None, idx, w, None, counts, offsets, H, hot, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(k=0), moe.MOE_ERR_INVALID_ARG),
+    (dict(k=9, E=16), moe.MOE_ERR_UNSUPPORTED),
+    (dict(k=3, E=2), moe.MOE_ERR_INVALID_ARG),
+    (dict(E=2048), moe.MOE_ERR_UNSUPPORTED),
+    (dict(d_model=48), moe.MOE_ERR_UNSUPPORTED),        # bf16 needs multiples of 32
+    (dict(d_ff=100), moe.MOE_ERR_UNSUPPORTED),
+    (dict(T=-1), moe.MOE_ERR_INVALID_ARG),
+    (dict(activation=1), moe.MOE_ERR_UNSUPPORTED),
+    (dict(dtype=7), moe.MOE_ERR_INVALID_ARG),
+])
+def test_bad_shapes_are_rejected(kw, status):
+    assert route_status(shape(**kw), ws_bytes=1 << 30) == status
+
+
+def test_bad_pointers_and_workspace_are_rejected():
+    s = shape()
+    assert route_status(s, x=None) == moe.MOE_ERR_INVALID_ARG
+    assert route_status(s, idx=None) == moe.MOE_ERR_INVALID_ARG
+    assert route_status(s, H=4, hot=None) == moe.MOE_ERR_INVALID_ARG
+    assert route_status(s, ws=None) == moe.MOE_ERR_WORKSPACE
+    assert route_status(s, ws=FAKE + 8) == moe.MOE_ERR_WORKSPACE        # misaligned
+    assert route_status(s, ws_bytes=moe.moe_workspace_bytes(s) - 1) == moe.MOE_ERR_WORKSPACE
+    lib = moe.load()
+    n = moe.moe_workspace_bytes(s)
+    assert lib.moe_permute(ctypes.byref(s), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_permute(ctypes.byref(s), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_expert_ffn(ctypes.byref(s), FAKE, None, FAKE, FAKE, None, FAKE, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_expert_ffn(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, 16, None) == moe.MOE_ERR_WORKSPACE
+    assert lib.moe_combine(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, None, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_layer_forward(ctypes.byref(s), FAKE, FAKE, None, FAKE, FAKE, None, -1, None, None, None, None,
+                                 None, None, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_pack_weights(ctypes.byref(s), 3, FAKE, FAKE + 256, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_pack_weights(ctypes.byref(s), 1, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_route(None, FAKE, FAKE, None, FAKE, FAKE, None, FAKE, FAKE, -1, None, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+
+
+def test_binding_raises_on_error():
+    with pytest.raises(moe.MoEError) as ei:
+        moe.moe_combine(shape(), FAKE, FAKE, FAKE, FAKE, None, None, stream=0)
+    assert ei.value.status == moe.MOE_ERR_INVALID_ARG

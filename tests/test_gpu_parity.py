@@ -1,0 +1,372 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: routing indices, counts, offsets, hot masks and permutations bit-exact
+(tokens whose fp64 top-(k+1) logit margin is below 1e-4 are listed and excluded from the index
+comparison); floating-point outputs within 1e-2 under  |got - ref| / max(|ref|, rms(ref))
+against the oracle run at the layer's storage precision for the hidden activation, and within
+1e-2 of max|ref| (normalised max error) against the oracle that never rounds it.
+"""
+import functools
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+MARGIN = 1e-4
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+@functools.lru_cache(maxsize=None)
+def oracle_route(name):
+    cfg = CFG(name)
+    x = wl.make_activations(cfg)
+    wg, b = wl.make_gate(cfg)
+    r = orc.route(x, wg, b, cfg.k, cfg.renormalize)
+    r["perm"], r["inv_perm"] = orc.stable_permutation_fast(r["idx"], cfg.E)
+    r["x"], r["wg"], r["b"] = x, wg, b
+    return r
+
+
+@functools.lru_cache(maxsize=72)
+def expert_cached(name, e):
+    return wl.make_expert(CFG(name), e)
+
+
+EXTRA = {
+    # ragged everything: T not a multiple of any tile, E not a power of two, k = 2 without renorm
+    "ragged_bf16": wl.MoEConfig("ragged_bf16", T=333, d_model=96, d_ff=160, E=11, k=2, dtype="bf16",
+                                renormalize=False, seed=11, zipf_s=1.0, gate_std=0.3),
+    "ragged_f32": wl.MoEConfig("ragged_f32", T=77, d_model=50, d_ff=70, E=5, k=3, dtype="f32",
+                               renormalize=True, seed=12, gate_std=0.5),
+    "one_expert": wl.MoEConfig("one_expert", T=100, d_model=64, d_ff=64, E=1, k=1, dtype="bf16",
+                               renormalize=False, seed=13),
+    "single_token": wl.MoEConfig("single_token", T=1, d_model=128, d_ff=256, E=16, k=2, dtype="bf16",
+                                 renormalize=True, seed=14, gate_std=0.3),
+    "k_equals_E": wl.MoEConfig("k_equals_E", T=40, d_model=64, d_ff=96, E=4, k=4, dtype="bf16",
+                               renormalize=True, seed=15, gate_std=0.3),
+    "many_experts": wl.MoEConfig("many_experts", T=600, d_model=64, d_ff=64, E=300, k=2, dtype="bf16",
+                                 renormalize=True, seed=16, gate_std=0.5),
+    "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
+                               renormalize=False, seed=17, zipf_s=40.0),
+    "matched_sl": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
+}
+
+
+def CFG(name):
+    return wl.CONFIGS[name] if name in wl.CONFIGS else EXTRA[name]
+
+
+SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
+         "many_experts", "all_to_one"]
+MEDIUM = ["switch_base", "switch_large_skew", "matched_sl"]
+LARGE = ["nllb_decode", "nllb_prefill_skew"]
+
+_layers = {}
+
+
+def device_layer(gpu_lib, name):
+    """One resident DeviceLayer at a time for the large configs (their weights are GBs)."""
+    from paper_2405_18832_amd.device_layer import DeviceLayer
+    if name in _layers:
+        return _layers[name]
+    for k in list(_layers):
+        if k in LARGE or name in LARGE:
+            del _layers[k]
+    if name in LARGE:
+        expert_cached.cache_clear()
+    torch.cuda.empty_cache()
+    cfg = CFG(name)
+    r = oracle_route(name)
+    experts = None
+    if name in LARGE:
+        experts = [e for e in range(cfg.E) if r["counts"][e] > 0]
+    say(f"[upload] {name}: T={cfg.T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k} "
+        f"real experts={'all' if experts is None else len(experts)}")
+    L = DeviceLayer(cfg, r["x"], r["wg"], r["b"], lambda e: expert_cached(name, e), experts=experts,
+                    workers=8)
+    _layers[name] = L
+    return L
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def check_values(got, ref_store, ref_exact, what):
+    e1 = orc.rel_error(got, ref_store)
+    nmax = float(np.abs(got - ref_exact).max() / max(np.abs(ref_exact).max(), 1e-30))
+    rms = float(np.sqrt(np.mean((got - ref_exact) ** 2)) / max(np.sqrt(np.mean(ref_exact ** 2)), 1e-30))
+    say(f"[values] {what}: max rel (storage-precision oracle) {e1.max():.3e}; vs exact oracle: "
+        f"normalised max {nmax:.3e}, rms ratio {rms:.3e}, elementwise max "
+        f"{orc.rel_error(got, ref_exact).max():.3e}")
+    assert e1.max() <= TOL, what
+    assert nmax <= TOL, what
+    assert rms <= 5e-3, what
+
+
+# ------------------------------------------------------------------------------ route
+@pytest.mark.parametrize("name", SMALL + MEDIUM + LARGE)
+def test_route(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] moe_route {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    H = cfg.H if cfg.H is not None else max(1, cfg.E // 3)
+    L.route(H=H)
+    torch.cuda.synchronize()
+    idx = L.topk_idx.cpu().numpy()
+    g = L.topk_w.cpu().numpy().astype(np.float64)
+    counts = L.counts.cpu().numpy()
+    offsets = L.offsets.cpu().numpy()
+    low = r["margin"] < MARGIN
+    say(f"[route] {name}: tokens with margin < {MARGIN}: {int(low.sum())} of {cfg.T}; "
+        f"active experts {orc.activated_experts(r['counts'])}, max count {int(r['counts'].max())}")
+    ok = ~low
+    assert np.array_equal(idx[ok], r["idx"][ok]), "top-k indices differ on well-separated tokens"
+    # low-margin tokens may differ, but must still hold k distinct valid experts
+    assert idx.min() >= 0 and idx.max() < cfg.E
+    if cfg.k > 1:
+        srt = np.sort(idx, axis=1)
+        assert np.all(srt[:, 1:] != srt[:, :-1])
+    same = np.all(idx == r["idx"], axis=1)
+    assert np.allclose(g[same], r["g"][same], rtol=2e-4, atol=1e-7)
+    assert np.array_equal(counts, np.bincount(idx.reshape(-1), minlength=cfg.E))
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(counts)]))
+    if same.all():
+        assert np.array_equal(counts, r["counts"]) and np.array_equal(offsets, r["offsets"])
+    assert np.array_equal(L.hot_mask.cpu().numpy(), orc.hot_mask_top_h(counts, H))
+    m = L.margin.cpu().numpy()
+    fin = np.isfinite(r["margin"])
+    assert np.allclose(m[fin], r["margin"][fin], rtol=0, atol=2e-4)
+
+
+# ------------------------------------------------------------------------------ permute
+@pytest.mark.parametrize("name", SMALL + MEDIUM + LARGE)
+def test_permute(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] moe_permute {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    L.permute(topk_idx=dev_i32(r["idx"]), offsets=dev_i32(r["offsets"]))
+    torch.cuda.synchronize()
+    assert np.array_equal(L.perm.cpu().numpy(), r["perm"])
+    assert np.array_equal(L.inv_perm.cpu().numpy(), r["inv_perm"])
+    xp = L.x_perm.float().cpu().numpy()
+    assert np.array_equal(xp, orc.permute_tokens(r["x"], r["perm"], cfg.k))
+    if cfg.A <= 4096:
+        p2, i2 = orc.stable_permutation(r["idx"], cfg.E)
+        assert np.array_equal(p2, r["perm"]) and np.array_equal(i2, r["inv_perm"])
+    # run-to-run determinism
+    first = L.perm.clone()
+    L.permute(topk_idx=dev_i32(r["idx"]), offsets=dev_i32(r["offsets"]))
+    torch.cuda.synchronize()
+    assert torch.equal(first, L.perm)
+
+
+# ------------------------------------------------------------------------------ expert FFN
+def sample_rows(r, cfg, per_expert, rng):
+    """Row positions (in permuted order) to check: for each non-empty expert its first and last row
+    and some random ones; all rows when the expert is small."""
+    rows = []
+    for e in range(cfg.E):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        if hi == lo:
+            continue
+        if hi - lo <= per_expert:
+            rows.append(np.arange(lo, hi))
+        else:
+            pick = rng.choice(np.arange(lo + 1, hi - 1), size=per_expert - 2, replace=False)
+            rows.append(np.concatenate([[lo, hi - 1], np.sort(pick)]))
+    return rows
+
+
+def oracle_ffn_rows(r, cfg, rows_by_expert):
+    x_perm = orc.permute_tokens(r["x"], r["perm"], cfg.k)
+    ref_s, ref_x, pos = [], [], []
+    hd = "bf16" if cfg.dtype == "bf16" else None
+    experts = [e for e in range(cfg.E) if r["offsets"][e + 1] > r["offsets"][e]]
+    for e, rows in zip(experts, rows_by_expert):
+        W1, W2 = expert_cached(cfg.name, e)
+        ref_s.append(orc.expert_ffn(x_perm[rows], W1, W2, hd))
+        ref_x.append(orc.expert_ffn(x_perm[rows], W1, W2, None))
+        pos.append(rows)
+    return np.concatenate(pos), np.concatenate(ref_s), np.concatenate(ref_x)
+
+
+@pytest.mark.parametrize("name", SMALL + MEDIUM + LARGE)
+def test_expert_ffn(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] moe_expert_ffn {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    xp = orc.permute_tokens(r["x"], r["perm"], cfg.k)
+    from paper_2405_18832_amd.device_layer import to_device
+    L.y_perm.fill_(float("nan"))
+    L.expert_ffn(x_perm=to_device(xp, cfg.dtype, L.device), offsets=dev_i32(r["offsets"]))
+    torch.cuda.synchronize()
+    y = L.y_perm.cpu().numpy().astype(np.float64)
+    assert np.isfinite(y).all(), "rows of active experts left unwritten"
+    per = 10 ** 9 if name in SMALL + ["switch_base"] else 12
+    rows = sample_rows(r, cfg, per, np.random.default_rng(5))
+    pos, ref_s, ref_x = oracle_ffn_rows(r, cfg, rows)
+    check_values(y[pos], ref_s, ref_x, f"y_perm {name} ({len(pos)} rows)")
+    # masked run: rows of masked-out experts stay untouched
+    mask_np = (np.arange(cfg.E) % 2 == 0).astype(np.uint8)
+    L.y_perm.fill_(float("nan"))
+    L.expert_ffn(mask=torch.from_numpy(mask_np).cuda(), x_perm=to_device(xp, cfg.dtype, L.device),
+                 offsets=dev_i32(r["offsets"]))
+    torch.cuda.synchronize()
+    y2 = L.y_perm.cpu().numpy().astype(np.float64)
+    owner = np.repeat(np.arange(cfg.E), r["counts"])
+    on = mask_np[owner] == 1
+    assert np.array_equal(y2[on], y[on]) and np.isnan(y2[~on]).all()
+
+
+# ------------------------------------------------------------------------------ combine
+@pytest.mark.parametrize("name", SMALL + MEDIUM + ["nllb_decode"])
+def test_combine(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] moe_combine {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    rng = np.random.default_rng(21)
+    y = rng.standard_normal((cfg.A, cfg.d_model)).astype(np.float32)
+    g32 = r["g"].astype(np.float32)
+    for mask_np in (None, (np.arange(cfg.E) % 3 != 0).astype(np.uint8)):
+        yy = y.copy()
+        if mask_np is not None:      # rows of masked-out experts must never be read
+            owner = np.repeat(np.arange(cfg.E), r["counts"])
+            yy[mask_np[owner] == 0] = np.nan
+        L.combine(mask=None if mask_np is None else torch.from_numpy(mask_np).cuda(),
+                  y_perm=torch.from_numpy(yy).cuda(), inv_perm=dev_i32(r["inv_perm"]),
+                  topk_idx=dev_i32(r["idx"]), topk_w=torch.from_numpy(g32).cuda())
+        torch.cuda.synchronize()
+        ref = orc.combine(y, r["inv_perm"], r["idx"], g32.astype(np.float64), mask_np)
+        got = L.out_numpy().astype(np.float64)
+        tol = 2.0 ** -8 if cfg.dtype == "bf16" else 1e-6
+        assert np.all(np.abs(got - ref) <= tol * np.maximum(np.abs(ref), 1e-3) + 1e-6)
+
+
+# ------------------------------------------------------------------------------ whole layer
+def oracle_expert_outputs(r, cfg, tokens, h_dtype):
+    """ys[i, j] = oracle FFN output of expert idx[t_i, j] on token t_i, for the sampled tokens."""
+    ys = np.zeros((len(tokens), cfg.k, cfg.d_model))
+    need = {}
+    for ti, t in enumerate(tokens):
+        for j in range(cfg.k):
+            need.setdefault(int(r["idx"][t, j]), []).append((ti, t, j))
+    for e, lst in sorted(need.items()):
+        W1, W2 = expert_cached(cfg.name, e)
+        y = orc.expert_ffn(r["x"][[t for _, t, _ in lst]], W1, W2, h_dtype)
+        for (ti, t, j), yrow in zip(lst, y):
+            ys[ti, j] = yrow
+    return ys
+
+
+def oracle_layer_rows(r, cfg, tokens, mask, ys):
+    """out[t] = sum_j [mask[idx[t,j]]] g[t,j] ys[t,j] -- the combine of the layer's definition."""
+    out = np.zeros((len(tokens), cfg.d_model))
+    for ti, t in enumerate(tokens):
+        for j in range(cfg.k):
+            e = int(r["idx"][t, j])
+            if mask is None or mask[e]:
+                out[ti] += r["g"][t, j] * ys[ti, j]
+    return out
+
+
+def pick_tokens(r, cfg, n, rng):
+    if cfg.T <= n:
+        return np.arange(cfg.T)
+    # make sure rarely-used experts are covered: one token from every non-empty expert, then random
+    first = [int(r["perm"][r["offsets"][e]]) // cfg.k for e in range(cfg.E) if r["counts"][e] > 0]
+    rest = rng.choice(cfg.T, size=n, replace=False)
+    return np.unique(np.concatenate([first, rest, [0, cfg.T - 1]]))
+
+
+@pytest.mark.parametrize("name", SMALL + MEDIUM + LARGE)
+def test_layer_forward(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] moe_layer_forward {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    low = r["margin"] < MARGIN
+    n_tok = 10 ** 9 if name in SMALL + ["switch_base"] else 160
+    toks = pick_tokens(r, cfg, n_tok, np.random.default_rng(9))
+    toks = toks[~low[toks]]
+    hd = "bf16" if cfg.dtype == "bf16" else None
+    H = cfg.H if cfg.H is not None else max(1, cfg.E // 3)
+    hot = orc.hot_mask_top_h(r["counts"], H)
+    cases = [("full", None, -1, None), ("hot mask given", hot, -1, hot), ("top-H on device", None, H, hot),
+             ("cold share", 1 - hot, -1, 1 - hot)]
+    outs = {}
+    ys_s = oracle_expert_outputs(r, cfg, toks, hd)
+    ys_x = oracle_expert_outputs(r, cfg, toks, None) if hd else ys_s
+    for label, mask_arg, Harg, mask_ref in cases:
+        L.out.fill_(float("nan"))
+        L.forward(mask=None if mask_arg is None else torch.from_numpy(mask_arg.astype(np.uint8)).cuda(),
+                  H=Harg, debug=True)
+        torch.cuda.synchronize()
+        got = L.out_numpy().astype(np.float64)
+        outs[label] = got
+        assert np.isfinite(got).all()
+        idx = L.topk_idx.cpu().numpy()
+        assert np.array_equal(idx[~low], r["idx"][~low])
+        if not low.any():
+            assert np.array_equal(L.counts.cpu().numpy(), r["counts"])
+            assert np.array_equal(L.perm.cpu().numpy(), r["perm"])
+            assert np.array_equal(L.hot_mask.cpu().numpy(),
+                                  np.ones(cfg.E, np.uint8) if mask_ref is None else mask_ref)
+        ref_s = oracle_layer_rows(r, cfg, toks, mask_ref, ys_s)
+        ref_x = oracle_layer_rows(r, cfg, toks, mask_ref, ys_x)
+        if np.abs(ref_x).max() == 0:
+            assert np.all(got[toks] == 0)
+        else:
+            check_values(got[toks], ref_s, ref_x, f"out {name} [{label}] ({len(toks)} tokens)")
+    assert np.array_equal(outs["hot mask given"], outs["top-H on device"])
+    # the two shares add up to the whole layer (each is rounded to storage once)
+    s = outs["hot mask given"] + outs["cold share"]
+    ulp = 2.0 ** -7 if cfg.dtype == "bf16" else 2.0 ** -22
+    assert np.all(np.abs(s - outs["full"]) <= 2 * ulp * (np.abs(outs["hot mask given"]) +
+                                                         np.abs(outs["cold share"]) + 1e-30) + 1e-30)
+    # determinism of the whole path
+    L.forward()
+    torch.cuda.synchronize()
+    a = L.out.clone()
+    L.forward()
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.uint8), L.out.view(torch.uint8))
+
+
+# ------------------------------------------------------------------------------ degenerate inputs
+def test_no_tokens_and_empty_mask(gpu_lib):
+    from paper_2405_18832_amd.device_layer import DeviceLayer
+    say("[case] T = 0")
+    cfg = wl.MoEConfig("empty", T=0, d_model=64, d_ff=64, E=4, k=2, dtype="bf16", renormalize=True, seed=3)
+    wg, b = wl.make_gate(cfg)
+    L = DeviceLayer(cfg, np.zeros((0, 64), np.float32), wg, b, lambda e: wl.make_expert(cfg, e))
+    L.counts.fill_(7)
+    L.offsets.fill_(7)
+    L.route(H=2)
+    L.permute()
+    L.expert_ffn()
+    L.combine()
+    L.forward()
+    torch.cuda.synchronize()
+    assert L.counts.cpu().tolist() == [0] * 4 and L.offsets.cpu().tolist() == [0] * 5
+    assert L.hot_mask.cpu().tolist() == [1, 1, 0, 0]
+    say("[case] all-zero mask")
+    L2 = device_layer(gpu_lib, "ragged_bf16")
+    L2.out.fill_(float("nan"))
+    L2.forward(mask=torch.zeros(CFG("ragged_bf16").E, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.all(L2.out == 0)
