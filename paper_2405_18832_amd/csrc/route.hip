@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(
                 if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
             }
             sel_v[j] = bv;
-            sel_i[j] = bi;
+            sel_i[j] = min(bi, E - 1);   // NaN logits must not produce an out-of-range expert
             if (j == 0) {
                 vmax = bv;
                 float part = 0.f;

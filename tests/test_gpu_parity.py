@@ -58,7 +58,7 @@ EXTRA = {
                                  renormalize=True, seed=16, gate_std=0.5),
     "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
                                renormalize=False, seed=17, zipf_s=40.0),
-    "matched_sl": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
+    "switch_large_skew_matched": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
 }
 
 
@@ -68,7 +68,7 @@ def CFG(name):
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
          "many_experts", "all_to_one"]
-MEDIUM = ["switch_base", "switch_large_skew", "matched_sl"]
+MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched"]
 LARGE = ["nllb_decode", "nllb_prefill_skew"]
 
 _layers = {}
