@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Throughput of the MoE FFN layer forward on one MI355X.
+
+A step is one pass of the whole hot path (moe_layer_forward: route -> permute -> expert FFN ->
+combine) over one batch of a synthetic layer; inputs and weights are resident in HBM before the
+timed region.  Prints ONE JSON line with tokens/s, the roofline figures of the dominant kernel
+(measured with HIP events recorded on the launch stream), and the CPU oracle timed on the host
+cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+import workloads as wl
+
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime (the library records them on its launch stream)."""
+
+    def __init__(self):
+        import torch      # the runtime torch loaded is the one the library launches on
+        self.hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def describe(cfg) -> str:
+    return (f"{cfg.name}: T={cfg.T} d_model={cfg.d_model} d_ff={cfg.d_ff} E={cfg.E} top-{cfg.k} "
+            f"{'renormalised' if cfg.renormalize else 'raw-prob'} gates, {cfg.dtype}, seed {cfg.seed}"
+            + (f", gate bias ln Zipf(s={cfg.zipf_s})" if cfg.zipf_s else ""))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="switch_base",
+                    choices=wl.CONFIG_ORDER + [n + "_matched" for n in ("switch_large_skew", "nllb_prefill_skew")])
+    ap.add_argument("--share", default="full", choices=["full", "hot"],
+                    help="full layer, or only the top-H hot experts' share (workloads with a hot mask)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="weight copies rotated through the timing loop (0 = enough for 2 GB between reuses)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2405_18832_amd as moe
+    from paper_2405_18832_amd.device_layer import DeviceLayer
+
+    moe.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    name = args.workload
+    cfg = wl.matched_noise(wl.CONFIGS[name[:-8]]) if name.endswith("_matched") else wl.CONFIGS[name]
+    K, W = args.steps, args.warmup
+    es = 2 if cfg.dtype == "bf16" else 4
+    log(f"[bench] workload {describe(cfg)}")
+
+    # ---- inputs into HBM --------------------------------------------------------------------
+    x = wl.make_activations(cfg)
+    wg, b = wl.make_gate(cfg)
+    cache = {}
+
+    def expert(e):
+        if e not in cache:
+            cache[e] = wl.make_expert(cfg, e)
+        return cache[e]
+
+    t0 = time.perf_counter()
+    small = cfg.E * cfg.d_model * cfg.d_ff <= 400e6
+    L = DeviceLayer(cfg, x, wg, b, expert, experts=None if small else [], device=dev, workers=16)
+    if not small:      # route on the device, then give the experts that receive tokens their seeded weights
+        L.route()
+        active = [e for e, c in enumerate(L.counts.cpu().tolist()) if c > 0]
+        L.upload_experts(expert, active, workers=16)
+    log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s")
+
+    hot = args.share == "hot"
+    if hot and cfg.H is None:
+        log("[bench] this workload defines no hot mask; use --share full")
+        return 2
+    H = cfg.H if hot else -1
+    L.forward(H=H, debug=True)
+    torch.cuda.synchronize()
+    counts = np.array(L.counts.cpu().tolist())
+    mask = np.array(L.hot_mask.cpu().tolist())
+    ran = (counts > 0) & (mask > 0)
+    n_active = int(ran.sum())
+    A_run = int(counts[ran].sum())
+    w_bytes_one = n_active * cfg.d_model * cfg.d_ff * es            # one product's weights
+    copies = args.copies or max(1, min(16, int(np.ceil(2e9 / max(1, 2 * w_bytes_one)))))
+    L.make_copies(copies)
+    log(f"[bench] experts run {n_active}/{cfg.E}, assignments run {A_run}/{cfg.A}, max tokens/expert "
+        f"{int(counts.max())}; {copies} weight copies rotated "
+        f"({copies * 2 * w_bytes_one / 1e9:.2f} GB of distinct weights between reuses)")
+
+    # ---- pass A: the timed steps -----------------------------------------------------------------
+    for i in range(W):
+        L.forward(H=H, copy=i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        L.forward(H=H, copy=i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / K * 1e3
+    tokens_s = cfg.T * K / dt
+
+    # ---- pass B: same loop with HIP events around the two grouped products ---------------------
+    hev = HipEvents()
+    evs = [(hev.create(), hev.create(), hev.create()) for _ in range(K)]
+    torch.cuda.synchronize()
+    for i in range(K):
+        moe.moe_set_profile_events(*evs[i])
+        L.forward(H=H, copy=i)
+    moe.moe_set_profile_events(None, None, None)
+    torch.cuda.synchronize()
+    g1 = np.array([hev.elapsed_ms(a, m) for a, m, _ in evs]) * 1e3      # us
+    g2 = np.array([hev.elapsed_ms(m, z) for _, m, z in evs]) * 1e3
+    for tr in evs:
+        for e in tr:
+            hev.destroy(e)
+
+    # ---- per-entry-point breakdown (torch events on the same stream) ---------------------------
+    def timed(fn, reps=50):
+        fn(0)
+        torch.cuda.synchronize()
+        a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            fn(i)
+        z.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(z) / reps * 1e3
+
+    mask_t = L.hot_mask.clone() if hot else None
+    L.route(H=H)
+    br = {"route_us": timed(lambda i: L.route(H=H)),
+          "permute_us": timed(lambda i: L.permute()),
+          "expert_ffn_us": timed(lambda i: L.expert_ffn(mask=mask_t, copy=i)),
+          "combine_us": timed(lambda i: L.combine(mask=mask_t))}
+
+    # ---- roofline of the dominant kernel ---------------------------------------------------------
+    d, f = cfg.d_model, cfg.d_ff
+    flops_one = 2.0 * A_run * d * f
+    kern = {
+        "w1_product": dict(us=float(g1.mean()), bytes=w_bytes_one + A_run * d * es, flops=flops_one),
+        "w2_product": dict(us=float(g2.mean()), bytes=w_bytes_one + A_run * d * 4, flops=flops_one),
+    }
+    dom = max(kern, key=lambda k_: kern[k_]["us"])
+    kd = kern[dom]
+    t_flop = kd["flops"] / (PEAK_BF16_TFLOPS * 1e12)
+    t_byte = kd["bytes"] / (PEAK_HBM_GBPS * 1e9)
+    if cfg.dtype != "bf16":
+        roof = None
+    elif t_flop > t_byte:
+        ach = kd["flops"] / (kd["us"] * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+    else:
+        ach = kd["bytes"] / (kd["us"] * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBPS, "traffic": None}
+    if roof is not None:
+        roof.update(kernel=f"ffn_stream_kernel ({dom})", kernel_us=kd["us"], kernel_us_min=float(
+            (g1 if dom == "w1_product" else g2).min()), algorithmic_bytes=kd["bytes"], flops=kd["flops"],
+            other_product_us=kern["w2_product" if dom == "w1_product" else "w1_product"]["us"])
+
+    layer_flops = 2.0 * cfg.T * d * cfg.E + 4.0 * A_run * d * f
+    layer_bytes = 2 * w_bytes_one + 2 * cfg.T * d * es + d * cfg.E * es
+    layer = {"tflops": layer_flops / (ms_step * 1e-3) / 1e12,
+             "useful_GBps": layer_bytes / (ms_step * 1e-3) / 1e9,
+             "useful_bytes": layer_bytes, "flops": layer_flops,
+             "experts_run": n_active, "assignments_run": A_run, **{k_: round(v, 2) for k_, v in br.items()}}
+
+    # ---- CPU oracle on a bounded sample of the same workload -------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        S = cfg.T if cfg.T <= 2048 else 256
+        xs = x[:S]
+        idx_s = np.array(L.topk_idx.cpu().tolist())[:S]
+        for e in sorted(set(idx_s.reshape(-1).tolist())):      # weight generation is not timed
+            expert(e)
+        mask_np = mask.astype(np.uint8) if hot else None
+        t0 = time.perf_counter()
+        ref = orc.layer_forward(xs, wg, b, expert, cfg.k, cfg.renormalize, mask_np,
+                                return_intermediates=True, h_dtype="bf16" if cfg.dtype == "bf16" else None)
+        cdt = time.perf_counter() - t0
+        ok = ref["margin"] >= 1e-4
+        got = L.out[:S].float().cpu().numpy()
+        err = float(orc.rel_error(got[ok], ref["out"][ok]).max()) if ok.any() else 0.0
+        cpu = {"value": S / cdt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"first {S} of {cfg.T} tokens, whole layer, fp64 numpy, {cdt:.2f} s "
+                         f"(host cores visible: {len(os.sched_getaffinity(0))})",
+               "gpu_vs_oracle_max_rel_err": err}
+        log(f"[bench] oracle: {S} tokens in {cdt:.2f} s on {threads} threads; GPU vs oracle max rel err {err:.3e}")
+
+    out = {"metric": "MoE-FFN tokens/s", "value": tokens_s, "unit": "tokens/s", "n_gpus": 1, "steps": K,
+           "warmup": W, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+           "config": {"workload": describe(cfg), "share": args.share, "weight_copies_rotated": copies},
+           "roofline": roof, "cpu_baseline": cpu, "layer": layer}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

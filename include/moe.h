@@ -140,6 +140,17 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
                        void* out, void* stream);
 
 /*
+ * Profiling aid for callers that time the two grouped products of the expert FFN separately
+ * (the paper reasons about an expert's cost product by product, Section 2.2 and Eq. 3-4).
+ * Each argument is a hipEvent_t created by the caller (as void*), or NULL.  Until the next
+ * call, every expert-FFN launch (from moe_expert_ffn or moe_layer_forward) records
+ * `before_w1` just before the first product's kernel, `between` after it, and `after_w2`
+ * after the second product's kernel, on the launch's stream.  Pass three NULLs to stop.
+ * Process-global and not thread-safe; events stay owned by the caller.
+ */
+void moe_set_profile_events(void* before_w1, void* between, void* after_w2);
+
+/*
  * The whole layer on one stream with no host synchronisation: route -> permute ->
  * expert FFN -> combine.  mask != NULL: only those experts run and are summed (the
  * hot share or the cold share of Section 3.3).  mask == NULL and H >= 0: the hot mask

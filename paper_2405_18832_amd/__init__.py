@@ -20,6 +20,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_MAX_K, MOE_MAX_E = 8, 1024
 
 EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
+           "moe_set_profile_events",
            "moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]
 
 
@@ -45,6 +46,10 @@ def load() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} not built; run python -m paper_2405_18832_amd.build")
+    # torch ships its own HIP runtime (same soname as the system one).  Import it first so that this
+    # library binds to the runtime torch's tensors and streams live in; loaded the other way round the
+    # process ends up with two runtimes and every launch on a torch stream fails.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     sp = ctypes.POINTER(moe_shape)
@@ -54,6 +59,8 @@ def load() -> ctypes.CDLL:
     lib.moe_workspace_bytes.argtypes = [sp]
     lib.moe_packed_weight_bytes.restype = sz
     lib.moe_packed_weight_bytes.argtypes = [sp]
+    lib.moe_set_profile_events.restype = None
+    lib.moe_set_profile_events.argtypes = [vp, vp, vp]
     lib.moe_pack_weights.restype = ctypes.c_int
     lib.moe_pack_weights.argtypes = [sp, i32, vp, vp, vp]
     lib.moe_route.restype = ctypes.c_int
@@ -118,6 +125,11 @@ def moe_workspace_bytes(shape: moe_shape) -> int:
 
 def moe_packed_weight_bytes(shape: moe_shape) -> int:
     return int(load().moe_packed_weight_bytes(ctypes.byref(shape)))
+
+
+def moe_set_profile_events(before_w1=None, between=None, after_w2=None) -> None:
+    """hipEvent_t handles as ints (or None)."""
+    load().moe_set_profile_events(before_w1, between, after_w2)
 
 
 def moe_pack_weights(shape, which, src, dst, stream=None) -> None:

@@ -310,6 +310,19 @@ static int pick_ksplit(int K) {
     return 1;
 }
 
+// events recorded around the two products when a caller asked for them (profiling aid)
+static hipEvent_t g_profile_events[3] = {nullptr, nullptr, nullptr};
+
+void set_profile_events(hipEvent_t e0, hipEvent_t e1, hipEvent_t e2) {
+    g_profile_events[0] = e0;
+    g_profile_events[1] = e1;
+    g_profile_events[2] = e2;
+}
+
+static hipError_t mark(int i, hipStream_t st) {
+    return g_profile_events[i] ? hipEventRecord(g_profile_events[i], st) : hipSuccess;
+}
+
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
                              Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st) {
@@ -323,6 +336,7 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long max_tiles = A / tile_rows + (E < A ? E : A);
+    if ((err = mark(0, st)) != hipSuccess) return err;
 
     if (s.dtype == MOE_F32) {
         const long g1 = max_tiles * ((f + 255) / 256), g2 = max_tiles * ((d + 255) / 256);
@@ -332,10 +346,13 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
                            static_cast<float*>(h_ws), tiles_ws, ntiles_ws, f, d);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
+        if ((err = mark(1, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(h_ws), static_cast<const float*>(w2), y_perm, tiles_ws,
                            ntiles_ws, d, f);
-        return hipGetLastError();
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        return mark(2, st);
     }
 
     const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
@@ -344,19 +361,19 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
     uint16_t* h = static_cast<uint16_t*>(h_ws);
     const int ks1 = pick_ksplit(d), ks2 = pick_ksplit(f);
     switch (tfmax) {
-        case 1:
-            err = launch_stream_k<1, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
-            if (err != hipSuccess) return err;
-            return launch_stream_k<1, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
-        case 2:
-            err = launch_stream_k<2, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
-            if (err != hipSuccess) return err;
-            return launch_stream_k<2, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
-        default:
-            err = launch_stream_k<4, 3, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st);
-            if (err != hipSuccess) return err;
-            return launch_stream_k<4, 3, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st);
+        case 1: err = launch_stream_k<1, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
+        default: err = launch_stream_k<4, 3, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
     }
+    if (err != hipSuccess) return err;
+    if ((err = mark(1, st)) != hipSuccess) return err;
+    switch (tfmax) {
+        case 1: err = launch_stream_k<1, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
+        default: err = launch_stream_k<4, 3, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
+    }
+    if (err != hipSuccess) return err;
+    return mark(2, st);
 }
 
 }  // namespace moe

@@ -47,26 +47,19 @@ class DeviceLayer:
         self.b_gate = None if b_gate is None else torch.from_numpy(
             np.ascontiguousarray(b_gate, dtype=np.float32)).to(dev)
 
+        # packed expert weights [E, f*d]; `copies` > 1 keeps identical clones that a timing loop can
+        # rotate through so that no step finds its weights in the last-level cache
+        self.w1 = torch.empty((E, f * d), dtype=td, device=dev)
+        self.w2 = torch.empty((E, d * f), dtype=td, device=dev)
+        self._one = make_shape(cfg.T, cfg.d_model, cfg.d_ff, 1, 1, cfg.dtype, cfg.renormalize)
         want = list(range(E)) if experts is None else sorted(set(int(e) for e in experts))
-        w1_plain = torch.empty((E, f, d), dtype=td, device=dev)
-        w2_plain = torch.empty((E, d, f), dtype=td, device=dev)
         if len(want) < E:
             gen = torch.Generator(device=dev).manual_seed(12345)
             for e in range(E):      # per expert: keeps the fp32 temporary small
-                w1_plain[e] = (torch.randn((f, d), device=dev, generator=gen) / d ** 0.5).to(td)
-                w2_plain[e] = (torch.randn((d, f), device=dev, generator=gen) / f ** 0.5).to(td)
-        with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
-            for i in range(0, len(want), workers):
-                es = want[i:i + workers]
-                for e, (w1, w2) in zip(es, pool.map(expert, es)):
-                    w1_plain[e].copy_(torch.from_numpy(w1).to(td))
-                    w2_plain[e].copy_(torch.from_numpy(w2).to(td))
-        self.w1 = torch.empty_like(w1_plain)
-        self.w2 = torch.empty_like(w2_plain)
-        moe_pack_weights(self.shape, 1, w1_plain, self.w1)
-        moe_pack_weights(self.shape, 2, w2_plain, self.w2)
-        torch.cuda.synchronize(dev)
-        del w1_plain, w2_plain
+                self.w1[e] = (torch.randn((f * d,), device=dev, generator=gen) / d ** 0.5).to(td)
+                self.w2[e] = (torch.randn((d * f,), device=dev, generator=gen) / f ** 0.5).to(td)
+        self.upload_experts(expert, want, workers)
+        self.weight_copies = [(self.w1, self.w2)]
 
         self.ws = torch.empty(max(256, moe_workspace_bytes(self.shape)), dtype=torch.uint8, device=dev)
         i32, f32 = torch.int32, torch.float32
@@ -82,6 +75,29 @@ class DeviceLayer:
         self.y_perm = torch.empty((A, d), dtype=f32, device=dev)
         self.out = torch.empty((T, d), dtype=td, device=dev)
 
+    def upload_experts(self, expert, experts, workers: int = 8) -> None:
+        """Host -> HBM copy and packing of the given experts' weights (one expert at a time)."""
+        cfg, dev, td = self.cfg, self.device, self.dtype
+        experts = list(experts)
+        if not experts:
+            return
+        s1 = torch.empty((cfg.d_ff, cfg.d_model), dtype=td, device=dev)
+        s2 = torch.empty((cfg.d_model, cfg.d_ff), dtype=td, device=dev)
+        with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
+            for i in range(0, len(experts), workers):
+                es = experts[i:i + workers]
+                for e, (w1, w2) in zip(es, pool.map(expert, es)):
+                    s1.copy_(torch.from_numpy(w1).to(td))
+                    s2.copy_(torch.from_numpy(w2).to(td))
+                    moe_pack_weights(self._one, 1, s1, self.w1[e])
+                    moe_pack_weights(self._one, 2, s2, self.w2[e])
+        torch.cuda.synchronize(dev)
+
+    def make_copies(self, n: int) -> None:
+        """Keep n identical copies of the packed weights (n >= 1)."""
+        self.weight_copies = [(self.w1, self.w2)] + [(self.w1.clone(), self.w2.clone())
+                                                     for _ in range(max(1, n) - 1)]
+
     # ---- the five entry points on this layer's buffers --------------------------------
     def route(self, H: int = -1):
         moe_route(self.shape, self.x, self.w_gate, self.b_gate, self.topk_idx, self.topk_w, self.margin,
@@ -92,8 +108,9 @@ class DeviceLayer:
                     self.offsets if offsets is None else offsets, self.perm, self.inv_perm, self.x_perm,
                     self.ws)
 
-    def expert_ffn(self, mask=None, x_perm=None, offsets=None):
-        moe_expert_ffn(self.shape, self.x_perm if x_perm is None else x_perm, self.w1, self.w2,
+    def expert_ffn(self, mask=None, x_perm=None, offsets=None, copy: int = 0):
+        w1, w2 = self.weight_copies[copy % len(self.weight_copies)]
+        moe_expert_ffn(self.shape, self.x_perm if x_perm is None else x_perm, w1, w2,
                        self.offsets if offsets is None else offsets, mask, self.y_perm, self.ws)
 
     def combine(self, mask=None, y_perm=None, inv_perm=None, topk_idx=None, topk_w=None):
@@ -102,13 +119,14 @@ class DeviceLayer:
                     self.topk_idx if topk_idx is None else topk_idx,
                     self.topk_w if topk_w is None else topk_w, mask, self.out)
 
-    def forward(self, mask=None, H: int = -1, debug: bool = False):
+    def forward(self, mask=None, H: int = -1, debug: bool = False, copy: int = 0):
+        w1, w2 = self.weight_copies[copy % len(self.weight_copies)]
         if debug:
-            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, self.w1, self.w2, mask, H,
+            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, w1, w2, mask, H,
                               self.out, self.topk_idx, self.topk_w, self.counts, self.perm, self.hot_mask,
                               self.ws)
         else:
-            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, self.w1, self.w2, mask, H,
+            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, w1, w2, mask, H,
                               self.out, ws=self.ws)
         return self.out
 
