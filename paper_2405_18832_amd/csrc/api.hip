@@ -84,7 +84,7 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, 
     if (st != MOE_OK) return st;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_route(*shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, offsets, H,
-                                 hot_mask, at<float>(ws, L.logits), static_cast<hipStream_t>(stream)));
+                                 hot_mask, at<int32_t>(ws, L.hist), static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* topk_idx, const int32_t* offsets,
@@ -144,25 +144,38 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     int32_t* idx = topk_idx ? topk_idx : at<int32_t>(ws, L.idx);
     float* gate = topk_w ? topk_w : at<float>(ws, L.gate);
     int32_t* cnt = counts ? counts : at<int32_t>(ws, L.counts);
-    int32_t* prm = perm ? perm : at<int32_t>(ws, L.perm);
     int32_t* offsets = at<int32_t>(ws, L.offsets);
     int32_t* inv = at<int32_t>(ws, L.inv_perm);
     uint8_t* own_mask = at<uint8_t>(ws, L.mask);
     const bool derive = (mask == nullptr && H >= 0);
     const uint8_t* used = mask ? mask : (derive ? own_mask : nullptr);
 
-    hipError_t e = launch_route(*shape, x, w_gate, gate_bias, idx, gate, nullptr, cnt, offsets,
-                                derive ? H : -1, derive ? own_mask : nullptr, at<float>(ws, L.logits), hs);
+    // route -> chunk histograms; one block turns them into counts, offsets, slot bases, the hot mask and the
+    // tile list; the chunks place their assignments; the first product gathers token rows through tokmap.
+    int32_t* hist = at<int32_t>(ws, L.hist);
+    int32_t* tokmap = at<int32_t>(ws, L.tokmap);
+    Tile* tiles = at<Tile>(ws, L.tiles);
+    int32_t* ntiles = at<int32_t>(ws, L.ntiles);
+    hipError_t e;
+    int nchunks = 0;
+    const int tok = route_chunk_tokens(*shape);
+    if (shape->T > 0) {
+        nchunks = (shape->T + tok - 1) / tok;
+        e = launch_route_fused(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, hs);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+    }
+    e = launch_scan_finalize(hist, nchunks, shape->E, cnt, offsets, derive ? H : -1, derive ? own_mask : nullptr,
+                             mask, tiles, ntiles, ffn_tile_rows(*shape), hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (hot_mask_out != nullptr) {
         e = launch_mask_out(used, hot_mask_out, shape->E, hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
     if (shape->T == 0) return MOE_OK;
-    e = launch_permute(*shape, x, idx, offsets, prm, inv, at<void>(ws, L.x_perm), at<int32_t>(ws, L.hist), hs);
+    e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
-    e = launch_expert_ffn(*shape, at<void>(ws, L.x_perm), w1, w2, offsets, used, at<float>(ws, L.y_perm),
-                          at<void>(ws, L.h), at<Tile>(ws, L.tiles), at<int32_t>(ws, L.ntiles), hs);
+    e = launch_expert_products(*shape, x, tokmap, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), tiles, ntiles,
+                               hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
     return from_hip(e);

@@ -49,8 +49,7 @@ struct Tile {
 
 // ---- workspace ----------------------------------------------------------------
 struct WsLayout {
-    size_t logits;     // float [T, E]
-    size_t hist;       // int32 [ceil(A/256), E]
+    size_t hist;       // int32 [ceil(T/16), E]  chunk histograms / slot bases of the counting sort
     size_t ntiles;     // int32 [64]  (element 0 used)
     size_t tiles;      // Tile [A/16 + E + 1]
     size_t h;          // dtype [A, f]
@@ -61,7 +60,7 @@ struct WsLayout {
     size_t perm;       // int32 [A]
     size_t inv_perm;   // int32 [A]
     size_t mask;       // uint8 [E]
-    size_t x_perm;     // dtype [A, d]
+    size_t tokmap;     // int32 [A]  token row of each permuted position
     size_t y_perm;     // float [A, d]
     size_t total;
 };
@@ -79,8 +78,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
         off += (bytes + 255) & ~static_cast<size_t>(255);
         return at;
     };
-    L.logits = take(static_cast<size_t>(s.T) * E * 4);
-    L.hist = take(((A + kPermChunk - 1) / kPermChunk) * E * 4);
+    L.hist = take(((static_cast<size_t>(s.T) + 15) / 16 + 1) * E * 4);
     L.ntiles = take(64 * 4);
     L.tiles = take((A / 16 + E + 1) * sizeof(Tile));
     L.h = take(A * s.d_ff * es);
@@ -91,7 +89,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.perm = take(A * 4);
     L.inv_perm = take(A * 4);
     L.mask = take(E);
-    L.x_perm = take(A * s.d_model * es);
+    L.tokmap = take(A * 4);
     L.y_perm = take(A * s.d_model * 4);
     L.total = off;
     return L;
@@ -100,8 +98,20 @@ inline WsLayout ws_layout(const moe_shape& s) {
 // ---- internal launchers (all asynchronous on `st`; return hipSuccess or the launch error)
 hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                         int32_t* idx, float* gate, float* margin, int32_t* counts,
-                        int32_t* offsets, int32_t H, uint8_t* hot_mask, float* logits_ws,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws,
                         hipStream_t st);
+int route_chunk_tokens(const moe_shape& s);
+hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st);
+hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
+                                uint8_t* hot_mask, const uint8_t* mask_in, Tile* tiles, int32_t* ntiles,
+                                int tile_rows, hipStream_t st);
+hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
+                        int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
+int ffn_tile_rows(const moe_shape& s);
+hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
+                                  const void* w2, float* y_perm, void* h_ws, const Tile* tiles,
+                                  const int32_t* ntiles, hipStream_t st);
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
                           int32_t* hist_ws, hipStream_t st);

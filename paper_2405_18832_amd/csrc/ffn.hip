@@ -99,9 +99,12 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 // over one k-slice; the KSPLIT wavefronts that share an output tile add their partial sums in
 // LDS in a fixed order.  Blocks are persistent and stride over (tile, n-group) units, whose
 // number is only known on the device.  PF k-steps of loads are kept in flight per wavefront.
+// With `rowmap`, row p of the activations is read from act[rowmap[p]] (the token gather of the
+// dispatch step folded into the first product); output rows are always in permuted order.
 // ---------------------------------------------------------------------------
 template <int TFMAX, int KSPLIT, int PF, bool FIRST>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
+                                                         const int32_t* __restrict__ rowmap,
                                                          const uint16_t* __restrict__ wpk,
                                                          void* __restrict__ outp,
                                                          const Tile* __restrict__ tiles,
@@ -140,7 +143,8 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
             const uint16_t* ap[TFMAX];
 #pragma unroll
             for (int tf = 0; tf < TFMAX; ++tf) {
-                const int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+                int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+                if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
                 ap[tf] = act + static_cast<size_t>(row) * K + g * 8;
             }
             bf16x8 a[PF][4], b[PF][TFMAX];
@@ -238,6 +242,7 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
 // ---------------------------------------------------------------------------
 template <bool FIRST>
 __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ act,
+                                                      const int32_t* __restrict__ rowmap,
                                                       const float* __restrict__ w,
                                                       float* __restrict__ outp,
                                                       const Tile* __restrict__ tiles,
@@ -250,7 +255,8 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
         if (n >= N) continue;
         const float* wr = w + (static_cast<size_t>(tl.expert) * N + n) * K;
         for (int i = 0; i < tl.rows; ++i) {
-            const float* ar = act + static_cast<size_t>(tl.row0 + i) * K;
+            const int src = rowmap ? rowmap[tl.row0 + i] : tl.row0 + i;
+            const float* ar = act + static_cast<size_t>(src) * K;
             float s = 0.f;
             for (int c = 0; c < K; ++c) s = fmaf(ar[c], wr[c], s);
             outp[static_cast<size_t>(tl.row0 + i) * N + n] = FIRST ? fmaxf(s, 0.f) : s;
@@ -274,8 +280,9 @@ int device_cu_count() {
 }
 
 template <int TFMAX, int KSPLIT, int PF, bool FIRST>
-static hipError_t launch_stream(const uint16_t* act, const uint16_t* wpk, void* outp, const Tile* tiles,
-                                const int32_t* ntiles, int N, int K, long max_units, hipStream_t st) {
+static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
+                                const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
+                                hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, PF, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -286,20 +293,23 @@ static hipError_t launch_stream(const uint16_t* act, const uint16_t* wpk, void* 
     long grid = static_cast<long>(device_cu_count()) * per_cu;
     if (grid > max_units) grid = max_units;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, wpk, outp, tiles, ntiles, N, K);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
+                       ntiles, N, K);
     return hipGetLastError();
 }
 
 template <int TFMAX, int PF, bool FIRST>
-static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const uint16_t* wpk, void* outp,
-                                  const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
-                                  hipStream_t st) {
+static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
+                                  void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
+                                  long max_tiles, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
-        return launch_stream<TFMAX, 4, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
+        return launch_stream<TFMAX, 4, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
     if (ksplit == 2)
-        return launch_stream<TFMAX, 2, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ((ngroups + 1) / 2), st);
-    return launch_stream<TFMAX, 1, PF, FIRST>(act, wpk, outp, tiles, ntiles, N, K, max_tiles * ((ngroups + 3) / 4), st);
+        return launch_stream<TFMAX, 2, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+                                                  max_tiles * ((ngroups + 1) / 2), st);
+    return launch_stream<TFMAX, 1, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+                                              max_tiles * ((ngroups + 3) / 4), st);
 }
 
 // k-steps of 32 per wavefront: split K over up to 4 wavefronts while each keeps >= 24 steps
@@ -323,57 +333,67 @@ static hipError_t mark(int i, hipStream_t st) {
     return g_profile_events[i] ? hipEventRecord(g_profile_events[i], st) : hipSuccess;
 }
 
-hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
-                             const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
-                             Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st) {
+// token fragments per tile: an expert holds at most T rows (a token picks an expert at most once)
+static int ffn_tfmax(const moe_shape& s) { return s.T <= 16 ? 1 : (s.T <= 32 ? 2 : 4); }
+
+int ffn_tile_rows(const moe_shape& s) { return s.dtype == MOE_BF16 ? 16 * ffn_tfmax(s) : 16; }
+
+// the two grouped products over an existing tile list
+hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
+                                  const void* w2, float* y_perm, void* h_ws, const Tile* tiles,
+                                  const int32_t* ntiles, hipStream_t st) {
     const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
-    // an expert holds at most T rows (a token picks an expert at most once)
-    int tfmax = 4;
-    if (s.dtype == MOE_BF16) tfmax = s.T <= 16 ? 1 : (s.T <= 32 ? 2 : 4);
-    const int tile_rows = s.dtype == MOE_BF16 ? 16 * tfmax : 16;
-    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, tiles_ws, ntiles_ws, E, A,
-                       tile_rows);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    const int tile_rows = ffn_tile_rows(s);
     const long max_tiles = A / tile_rows + (E < A ? E : A);
+    hipError_t err;
     if ((err = mark(0, st)) != hipSuccess) return err;
 
     if (s.dtype == MOE_F32) {
         const long g1 = max_tiles * ((f + 255) / 256), g2 = max_tiles * ((d + 255) / 256);
         const long cap = static_cast<long>(device_cu_count()) * 8;
         hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(static_cast<unsigned>(g1 < cap ? g1 : cap)), dim3(256), 0, st,
-                           static_cast<const float*>(x_perm), static_cast<const float*>(w1),
-                           static_cast<float*>(h_ws), tiles_ws, ntiles_ws, f, d);
+                           static_cast<const float*>(act), rowmap, static_cast<const float*>(w1),
+                           static_cast<float*>(h_ws), tiles, ntiles, f, d);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
         if ((err = mark(1, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
-                           static_cast<const float*>(h_ws), static_cast<const float*>(w2), y_perm, tiles_ws,
-                           ntiles_ws, d, f);
+                           static_cast<const float*>(h_ws), static_cast<const int32_t*>(nullptr),
+                           static_cast<const float*>(w2), y_perm, tiles, ntiles, d, f);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
         return mark(2, st);
     }
 
-    const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
+    const uint16_t* xp = static_cast<const uint16_t*>(act);
     const uint16_t* p1 = static_cast<const uint16_t*>(w1);
     const uint16_t* p2 = static_cast<const uint16_t*>(w2);
     uint16_t* h = static_cast<uint16_t*>(h_ws);
     const int ks1 = pick_ksplit(d), ks2 = pick_ksplit(f);
-    switch (tfmax) {
-        case 1: err = launch_stream_k<1, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, 4, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
-        default: err = launch_stream_k<4, 3, true>(ks1, xp, p1, h, tiles_ws, ntiles_ws, f, d, max_tiles, st); break;
+    switch (ffn_tfmax(s)) {
+        case 1: err = launch_stream_k<1, 4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, 4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+        default: err = launch_stream_k<4, 3, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(1, st)) != hipSuccess) return err;
-    switch (tfmax) {
-        case 1: err = launch_stream_k<1, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, 4, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
-        default: err = launch_stream_k<4, 3, false>(ks2, h, p2, y_perm, tiles_ws, ntiles_ws, d, f, max_tiles, st); break;
+    switch (ffn_tfmax(s)) {
+        case 1: err = launch_stream_k<1, 4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, 4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        default: err = launch_stream_k<4, 3, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(2, st);
+}
+
+hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
+                             const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
+                             Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, tiles_ws, ntiles_ws, s.E,
+                       s.T * s.k, ffn_tile_rows(s));
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    return launch_expert_products(s, x_perm, nullptr, w1, w2, y_perm, h_ws, tiles_ws, ntiles_ws, st);
 }
 
 }  // namespace moe

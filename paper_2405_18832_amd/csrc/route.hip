@@ -2,190 +2,233 @@
 // lowest-index tie-break, gate weights, per-expert token histogram, prefix sums and the
 // top-H hot mask (paper Section 2.1 for the gating network, Section 3.3 for the token
 // counts and the hot set).
+//
+// Two kernels.  route_fused_kernel: one block per chunk of 16*TF tokens computes the chunk's
+// logits into LDS, picks each token's experts there and leaves the chunk's per-expert
+// histogram in the workspace.  scan_finalize_kernel: one block turns the chunk histograms
+// into counts, prefix sums (per expert over chunks, and over experts), the hot mask and the
+// expert tile list.  Nothing is ordered through atomics on global memory, so every output
+// is the same on every run.
 #include "common.hpp"
 
 namespace moe {
 
-// ---------------------------------------------------------------------------
-// logits, bf16 storage: MFMA 16x16x32 with the gate rows as the A operand and the token
-// rows as the B operand, so a lane ends up with 4 consecutive experts of one token.
-// Block = 4 wavefronts on the same 16*TF tokens; wave w takes experts [64w, 64w+64) of
-// every 256-expert chunk.  Operands come straight from global memory (the gate matrix is
-// L2-resident, x is read once).
-// ---------------------------------------------------------------------------
-template <int TF>
-__global__ __launch_bounds__(256) void gate_logits_bf16_kernel(
-    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
-    const float* __restrict__ bias, float* __restrict__ logits, int32_t* __restrict__ counts,
-    int T, int d, int E) {
-    if (blockIdx.x == 0)
-        for (int e = threadIdx.x; e < E; e += blockDim.x) counts[e] = 0;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int r = lane & 15, g = lane >> 4;
-    const int t0 = blockIdx.x * (16 * TF);
-    const uint16_t* xrow[TF];
-#pragma unroll
-    for (int tf = 0; tf < TF; ++tf) {
-        int t = min(t0 + tf * 16 + r, T - 1);
-        xrow[tf] = x + static_cast<size_t>(t) * d + g * 8;
-    }
-    for (int ec = 0; ec < E; ec += 256) {
-        const int eb = ec + wave * 64;
-        if (eb >= E) continue;
-        const uint16_t* wrow[4];
-#pragma unroll
-        for (int nf = 0; nf < 4; ++nf) {
-            int e = min(eb + nf * 16 + r, E - 1);
-            wrow[nf] = wg + static_cast<size_t>(e) * d + g * 8;
-        }
-        f32x4 acc[4][TF];
-#pragma unroll
-        for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-            for (int tf = 0; tf < TF; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-        for (int k0 = 0; k0 < d; k0 += 32) {
-            bf16x8 a[4], b[TF];
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf) a[nf] = *reinterpret_cast<const bf16x8*>(wrow[nf] + k0);
-#pragma unroll
-            for (int tf = 0; tf < TF; ++tf) b[tf] = *reinterpret_cast<const bf16x8*>(xrow[tf] + k0);
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-                for (int tf = 0; tf < TF; ++tf)
-                    acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nf], b[tf], acc[nf][tf], 0, 0, 0);
-        }
-#pragma unroll
-        for (int tf = 0; tf < TF; ++tf) {
-            const int t = t0 + tf * 16 + r;
-            if (t >= T) continue;
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e = eb + nf * 16 + g * 4 + i;
-                    if (e < E) logits[static_cast<size_t>(t) * E + e] = acc[nf][tf][i] + (bias ? bias[e] : 0.f);
-                }
-        }
-    }
-}
-
-// logits, fp32 storage: one thread per (token, expert), sequential fp32 FMA over d.
-__global__ void gate_logits_f32_kernel(const float* __restrict__ x, const float* __restrict__ wg,
-                                       const float* __restrict__ bias, float* __restrict__ logits,
-                                       int32_t* __restrict__ counts, int T, int d, int E) {
-    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (blockIdx.x == 0)
-        for (int e = threadIdx.x; e < E; e += blockDim.x) counts[e] = 0;
-    if (i >= static_cast<size_t>(T) * E) return;
-    const int t = static_cast<int>(i / E), e = static_cast<int>(i % E);
-    const float* xr = x + static_cast<size_t>(t) * d;
-    const float* wr = wg + static_cast<size_t>(e) * d;
-    float s = 0.f;
-    for (int c = 0; c < d; ++c) s = fmaf(xr[c], wr[c], s);
-    logits[i] = s + (bias ? bias[e] : 0.f);
-}
+constexpr int kMaxRounds = MOE_MAX_K + 1;
 
 // ---------------------------------------------------------------------------
-// softmax + top-k: one wavefront per token, lanes strided over the experts.  k+1 rounds
-// of a (value, index) arg-max across the wave; on equal values the lower index wins, in
-// the lane-local scan and in every exchange, so the order is exactly "descending logit,
-// ties by lowest expert index".  Token counts go through an LDS histogram per block and
-// one integer atomic per non-empty bin.
+// top-k of one token from its logits row in LDS, by a group of 16 lanes (4 tokens per wave).
+// k+1 rounds of a (value, index) arg-max; on equal values the lower index wins, in the
+// lane-local scan and in every exchange, so the order is "descending logit, ties by lowest
+// expert index".  A winner is retired by overwriting its logit with -inf.
 // ---------------------------------------------------------------------------
-constexpr int kRouteTokensPerBlock = 64;
-
-__global__ __launch_bounds__(256) void softmax_topk_kernel(
-    const float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    float* __restrict__ margin, int32_t* __restrict__ counts, int T, int E, int k, int renorm) {
-    __shared__ int32_t hist[MOE_MAX_E];
-    for (int e = threadIdx.x; e < E; e += blockDim.x) hist[e] = 0;
-    __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int tbeg = blockIdx.x * kRouteTokensPerBlock;
-    const int tend = min(T, tbeg + kRouteTokensPerBlock);
-    constexpr int C = MOE_MAX_E / 64;
+__device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, int k, int renorm, int sub,
+                                              bool live, int32_t* __restrict__ idx_out,
+                                              float* __restrict__ w_out, float* __restrict__ margin_out,
+                                              int32_t* __restrict__ hist) {
     const float NEG = -__builtin_huge_valf();
-    for (int t = tbeg + wave; t < tend; t += 4) {
-        float v[C];
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            const int e = lane + 64 * c;
-            v[c] = (e < E) ? logits[static_cast<size_t>(t) * E + e] : NEG;
+    float sel_v[kMaxRounds];
+    int sel_i[kMaxRounds];
+    const int rounds = min(k + 1, E);
+    float vmax = 0.f, denom = 1.f;
+#pragma unroll 1
+    for (int j = 0; j < rounds; ++j) {
+        float bv = NEG;
+        int bi = 0x7fffffff;
+        for (int e = sub; e < E; e += 16) {
+            const float v = row[e];
+            if (v > bv || bi == 0x7fffffff) { bv = v; bi = e; }
         }
-        float sel_v[MOE_MAX_K + 1];
-        int sel_i[MOE_MAX_K + 1];
-        const int rounds = min(k + 1, E);
-        float vmax = 0.f, denom = 0.f;
-        for (int j = 0; j < rounds; ++j) {
-            float bv = NEG;
-            int bi = 0x7fffffff;
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const int e = lane + 64 * c;
-                if (e < E && (v[c] > bv || bi == 0x7fffffff)) { bv = v[c]; bi = e; }
-            }
-#pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) {
-                const float ov = __shfl_xor(bv, s);
-                const int oi = __shfl_xor(bi, s);
-                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-            }
-            sel_v[j] = bv;
-            sel_i[j] = min(bi, E - 1);   // NaN logits must not produce an out-of-range expert
-            if (j == 0) {
-                vmax = bv;
-                float part = 0.f;
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (lane + 64 * c < E) part += expf(v[c] - vmax);
-#pragma unroll
-                for (int s = 32; s >= 1; s >>= 1) part += __shfl_xor(part, s);
-                denom = part;
-            }
-            // retire the winner: its owner lane drops it from later rounds
-#pragma unroll
-            for (int c = 0; c < C; ++c)
-                if (lane + 64 * c == bi) v[c] = NEG;
+        for (int s = 8; s >= 1; s >>= 1) {
+            const float ov = __shfl_xor(bv, s);
+            const int oi = __shfl_xor(bi, s);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
         }
-        if (lane == 0) {
-            float p[MOE_MAX_K];
-            float psum = 0.f;
-            for (int j = 0; j < k; ++j) {
+        bi = min(bi, E - 1);          // NaN logits must not produce an out-of-range expert
+        if (j == 0) {
+            vmax = bv;
+            float part = 0.f;
+            for (int e = sub; e < E; e += 16) part += expf(row[e] - vmax);
+#pragma unroll
+            for (int s = 8; s >= 1; s >>= 1) part += __shfl_xor(part, s);
+            denom = part;
+        }
+#pragma unroll
+        for (int q = 0; q < kMaxRounds; ++q)
+            if (q == j) { sel_v[q] = bv; sel_i[q] = bi; }
+        if (sub == 0) row[bi] = NEG;
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (live && sub == 0) {
+        float p[MOE_MAX_K];
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j)
+            if (j < k) {
                 p[j] = expf(sel_v[j] - vmax) / denom;
                 psum += p[j];
             }
-            for (int j = 0; j < k; ++j) {
-                topk_idx[static_cast<size_t>(t) * k + j] = sel_i[j];
-                topk_w[static_cast<size_t>(t) * k + j] = renorm ? p[j] / psum : p[j];
-                atomicAdd(&hist[sel_i[j]], 1);
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j)
+            if (j < k) {
+                idx_out[j] = sel_i[j];
+                w_out[j] = renorm ? p[j] / psum : p[j];
+                atomicAdd(&hist[sel_i[j]], 1);      // LDS, integer: order does not matter
             }
-            if (margin) {
-                float m = __builtin_huge_valf();
-                for (int j = 0; j + 1 < rounds; ++j) m = fminf(m, sel_v[j] - sel_v[j + 1]);
-                margin[t] = m;
-            }
+        if (margin_out) {
+            float m = __builtin_huge_valf();
+#pragma unroll
+            for (int j = 0; j + 1 < kMaxRounds; ++j)
+                if (j + 1 < rounds) m = fminf(m, sel_v[j] - sel_v[j + 1]);
+            *margin_out = m;
         }
     }
-    __syncthreads();
-    for (int e = threadIdx.x; e < E; e += blockDim.x)
-        if (hist[e] != 0) atomicAdd(&counts[e], hist[e]);
 }
 
 // ---------------------------------------------------------------------------
-// prefix sums of the counts and the top-H hot mask (rank by count, ties by lowest index).
-// One block of 1024 threads, one thread per expert.
+// route_fused_kernel<ST, TF>: block = 4 wavefronts, chunk = 16*TF tokens.
+//  bf16: MFMA 16x16x32 with gate rows as the A operand and token rows as the B operand (a lane
+//  ends up with 4 consecutive experts of one token); the 4 wavefronts split the contraction
+//  (each reads its own quarter of every row, so x and the gate matrix cross L1 once per block)
+//  and add their partial logits into LDS one after the other, in wave order.
+//  fp32: plain FMA dot products, one (token, expert) pair per thread and pass.
+// Dynamic LDS: logits [16*TF][E+1] floats, then the histogram [E] ints.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void route_finalize_kernel(const int32_t* __restrict__ counts,
-                                                              int32_t* __restrict__ offsets,
-                                                              uint8_t* __restrict__ hot_mask, int E,
-                                                              int H) {
-    __shared__ int32_t c[MOE_MAX_E];
+template <typename ST, int TF>
+__global__ __launch_bounds__(256) void route_fused_kernel(const ST* __restrict__ x, const ST* __restrict__ wg,
+                                                          const float* __restrict__ bias,
+                                                          int32_t* __restrict__ topk_idx,
+                                                          float* __restrict__ topk_w, float* __restrict__ margin,
+                                                          int32_t* __restrict__ chunk_hist, int T, int d, int E,
+                                                          int k, int renorm) {
+    constexpr int TOK = 16 * TF;
+    extern __shared__ float lds[];
+    const int Ep = E + 1;
+    float* L = lds;
+    int32_t* hist = reinterpret_cast<int32_t*>(lds + TOK * Ep);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t0 = blockIdx.x * TOK;
+    for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
+
+    if constexpr (sizeof(ST) == 2) {
+        const int r = lane & 15, g = lane >> 4;
+        const int ksteps = d >> 5;
+        const int per = (ksteps + 3) >> 2;
+        const int kb0 = min(ksteps, wave * per), kb1 = min(ksteps, kb0 + per);
+        const uint16_t* xrow[TF];
+#pragma unroll
+        for (int tf = 0; tf < TF; ++tf)
+            xrow[tf] = reinterpret_cast<const uint16_t*>(x) + static_cast<size_t>(min(t0 + tf * 16 + r, T - 1)) * d + g * 8;
+        for (int ec = 0; ec < E; ec += 128) {
+            const int nfr = min(8, (E - ec + 15) >> 4);
+            const uint16_t* wrow[8];
+#pragma unroll
+            for (int nf = 0; nf < 8; ++nf)
+                wrow[nf] = reinterpret_cast<const uint16_t*>(wg) + static_cast<size_t>(min(ec + nf * 16 + r, E - 1)) * d + g * 8;
+            f32x4 acc[8][TF];
+#pragma unroll
+            for (int nf = 0; nf < 8; ++nf)
+#pragma unroll
+                for (int tf = 0; tf < TF; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+            for (int kb = kb0; kb < kb1; ++kb) {
+                bf16x8 b[TF];
+#pragma unroll
+                for (int tf = 0; tf < TF; ++tf) b[tf] = *reinterpret_cast<const bf16x8*>(xrow[tf] + kb * 32);
+#pragma unroll
+                for (int nf = 0; nf < 8; ++nf)
+                    if (nf < nfr) {
+                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(wrow[nf] + kb * 32);
+#pragma unroll
+                        for (int tf = 0; tf < TF; ++tf)
+                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[tf], acc[nf][tf], 0, 0, 0);
+                    }
+            }
+            for (int w = 0; w < 4; ++w) {        // partial sums are added in wave order: deterministic
+                if (wave == w) {
+#pragma unroll
+                    for (int nf = 0; nf < 8; ++nf)
+                        if (nf < nfr) {
+#pragma unroll
+                            for (int tf = 0; tf < TF; ++tf)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const int e = ec + nf * 16 + g * 4 + i;
+                                    if (e < E) {
+                                        float* p = L + (tf * 16 + r) * Ep + e;
+                                        const float v = acc[nf][tf][i];
+                                        *p = (w == 0) ? v + (bias ? bias[e] : 0.f) : *p + v;
+                                    }
+                                }
+                        }
+                }
+                __syncthreads();
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < TOK * E; i += 256) {
+            const int tl = i / E, e = i % E;
+            const float* xr = reinterpret_cast<const float*>(x) + static_cast<size_t>(min(t0 + tl, T - 1)) * d;
+            const float* wr = reinterpret_cast<const float*>(wg) + static_cast<size_t>(e) * d;
+            float s = 0.f;
+            for (int c = 0; c < d; ++c) s = fmaf(xr[c], wr[c], s);
+            L[tl * Ep + e] = s + (bias ? bias[e] : 0.f);
+        }
+        __syncthreads();
+    }
+
+    const int grp = lane >> 4, sub = lane & 15;
+#pragma unroll 1
+    for (int pass = 0; pass < TF; ++pass) {
+        const int tl = pass * 16 + wave * 4 + grp;
+        const int t = t0 + tl;
+        const bool live = t < T;
+        const size_t o = static_cast<size_t>(live ? t : 0) * k;
+        topk_from_lds(L + tl * Ep, E, k, renorm, sub, live, topk_idx + o, topk_w + o,
+                      margin ? margin + (live ? t : 0) : nullptr, hist);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
+}
+
+// ---------------------------------------------------------------------------
+// scan_finalize_kernel: one block of 1024 threads (16 wavefronts).
+//  phase 1: for every expert, exclusive prefix sum of its chunk histogram over the chunks, in
+//           place (the slot bases of the counting sort); the total is the expert's token count.
+//  phase 2: prefix sums over experts -> offsets; top-H hot mask (rank by count, ties by lowest
+//           index); the tile list of the expert FFN (every active, masked-in expert's segment
+//           cut into tiles of `tile_rows` rows).
+// Any output pointer may be NULL.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
+                                                             int E, int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets, int H,
+                                                             uint8_t* __restrict__ hot_mask,
+                                                             const uint8_t* __restrict__ mask_in,
+                                                             Tile* __restrict__ tiles, int32_t* __restrict__ ntiles,
+                                                             int tile_rows) {
+    __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int e = wave; e < E; e += 16) {
+        int carry = 0;
+        for (int c0 = 0; c0 < nchunks; c0 += 64) {
+            const int c = c0 + lane;
+            const int v = (c < nchunks) ? chunk_hist[static_cast<size_t>(c) * E + e] : 0;
+            int incl = v;
+#pragma unroll
+            for (int s = 1; s < 64; s <<= 1) {
+                const int o = __shfl_up(incl, s);
+                if (lane >= s) incl += o;
+            }
+            if (c < nchunks) chunk_hist[static_cast<size_t>(c) * E + e] = carry + incl - v;
+            carry += __shfl(incl, 63);
+        }
+        if (lane == 0) cnt[e] = carry;
+    }
+    __syncthreads();
     const int e = threadIdx.x;
-    const int mine = (e < E) ? counts[e] : 0;
-    c[e] = mine;
+    const int mine = (e < E) ? cnt[e] : 0;
     scan[e] = mine;
     __syncthreads();
     for (int s = 1; s < MOE_MAX_E; s <<= 1) {
@@ -194,13 +237,43 @@ __global__ __launch_bounds__(1024) void route_finalize_kernel(const int32_t* __r
         scan[e] += add;
         __syncthreads();
     }
-    if (e < E) offsets[e] = scan[e] - mine;
-    if (e == E - 1) offsets[E] = scan[e];
-    if (hot_mask != nullptr && H >= 0 && e < E) {
-        int rank = 0;
-        for (int o = 0; o < E; ++o) rank += (c[o] > mine || (c[o] == mine && o < e)) ? 1 : 0;
-        hot_mask[e] = rank < H ? 1 : 0;
+    const int row0 = scan[e] - mine;
+    if (e < E) {
+        if (counts) counts[e] = mine;
+        if (offsets) offsets[e] = row0;
     }
+    if (e == E - 1 && offsets) offsets[E] = scan[e];
+    bool on = e < E;
+    if (H >= 0 && e < E) {
+        int rank = 0;
+        for (int o = 0; o < E; ++o) rank += (cnt[o] > mine || (cnt[o] == mine && o < e)) ? 1 : 0;
+        on = rank < H;
+        if (hot_mask) hot_mask[e] = on ? 1 : 0;
+    } else if (mask_in != nullptr && e < E) {
+        on = mask_in[e] != 0;
+    }
+    if (tiles == nullptr) return;      // uniform: every thread sees the same pointer
+    __syncthreads();
+    const int m = on ? mine : 0;
+    const int nt = (m + tile_rows - 1) / tile_rows;
+    scan[e] = nt;
+    __syncthreads();
+    for (int s = 1; s < MOE_MAX_E; s <<= 1) {
+        const int add = (e >= s) ? scan[e - s] : 0;
+        __syncthreads();
+        scan[e] += add;
+        __syncthreads();
+    }
+    const int base = scan[e] - nt;
+    for (int i = 0; i < nt; ++i) {
+        Tile t;
+        t.expert = e;
+        t.row0 = row0 + i * tile_rows;
+        t.rows = min(tile_rows, m - i * tile_rows);
+        t.pad = 0;
+        tiles[base + i] = t;
+    }
+    if (e == MOE_MAX_E - 1) ntiles[0] = scan[e];
 }
 
 __global__ void mask_out_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int E) {
@@ -213,48 +286,67 @@ hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hip
     return hipGetLastError();
 }
 
-__global__ void zero_i32_kernel(int32_t* __restrict__ p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+int route_chunk_tokens(const moe_shape& s) {
+    return (s.dtype == MOE_BF16 && s.T >= 4096 && s.E <= 128) ? 64 : 16;
+}
+
+hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
+    const int T = s.T, d = s.d_model, E = s.E;
+    const int tok = route_chunk_tokens(s);
+    const unsigned grid = static_cast<unsigned>((T + tok - 1) / tok);
+    const size_t lds = static_cast<size_t>(tok) * (E + 1) * 4 + static_cast<size_t>(E) * 4;
+    if (lds > 48 * 1024) {      // more LDS than the default per-block limit: raise it for these kernels
+        hipError_t ea = hipSuccess;
+        if (s.dtype == MOE_BF16 && tok == 64)
+            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<uint16_t, 4>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        else if (s.dtype == MOE_BF16)
+            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<uint16_t, 1>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        else
+            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<float, 1>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (ea != hipSuccess) return ea;
+    }
+    if (s.dtype == MOE_BF16) {
+        const uint16_t* xp = static_cast<const uint16_t*>(x);
+        const uint16_t* wp = static_cast<const uint16_t*>(w_gate);
+        if (tok == 64)
+            hipLaunchKernelGGL((route_fused_kernel<uint16_t, 4>), dim3(grid), dim3(256), lds, st, xp, wp, bias, idx,
+                               gate, margin, chunk_hist, T, d, E, s.k, s.renormalize);
+        else
+            hipLaunchKernelGGL((route_fused_kernel<uint16_t, 1>), dim3(grid), dim3(256), lds, st, xp, wp, bias, idx,
+                               gate, margin, chunk_hist, T, d, E, s.k, s.renormalize);
+    } else {
+        hipLaunchKernelGGL((route_fused_kernel<float, 1>), dim3(grid), dim3(256), lds, st,
+                           static_cast<const float*>(x), static_cast<const float*>(w_gate), bias, idx, gate, margin,
+                           chunk_hist, T, d, E, s.k, s.renormalize);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
+                                uint8_t* hot_mask, const uint8_t* mask_in, Tile* tiles, int32_t* ntiles,
+                                int tile_rows, hipStream_t st) {
+    hipLaunchKernelGGL(scan_finalize_kernel, dim3(1), dim3(1024), 0, st, chunk_hist, nchunks, E, counts, offsets, H,
+                       hot_mask, mask_in, tiles, ntiles, tile_rows);
+    return hipGetLastError();
 }
 
 hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                         int32_t* idx, float* gate, float* margin, int32_t* counts,
-                        int32_t* offsets, int32_t H, uint8_t* hot_mask, float* logits_ws,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws,
                         hipStream_t st) {
-    const int T = s.T, d = s.d_model, E = s.E;
-    if (T == 0) {   // no tokens: all counts and offsets are zero
-        hipLaunchKernelGGL(zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, counts, E);
-        hipError_t e0 = hipGetLastError();
-        if (e0 != hipSuccess) return e0;
-        hipLaunchKernelGGL(route_finalize_kernel, dim3(1), dim3(1024), 0, st, counts, offsets, hot_mask, E, H);
-        return hipGetLastError();
+    int nchunks = 0;
+    if (s.T > 0) {
+        const int tok = route_chunk_tokens(s);
+        nchunks = (s.T + tok - 1) / tok;
+        hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, st);
+        if (err != hipSuccess) return err;
     }
-    if (s.dtype == MOE_BF16) {
-        if (T >= 1024) {
-            hipLaunchKernelGGL(gate_logits_bf16_kernel<4>, dim3((T + 63) / 64), dim3(256), 0, st,
-                               static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_gate),
-                               bias, logits_ws, counts, T, d, E);
-        } else {
-            hipLaunchKernelGGL(gate_logits_bf16_kernel<1>, dim3((T + 15) / 16), dim3(256), 0, st,
-                               static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_gate),
-                               bias, logits_ws, counts, T, d, E);
-        }
-    } else {
-        const size_t n = static_cast<size_t>(T) * E;
-        hipLaunchKernelGGL(gate_logits_f32_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256),
-                           0, st, static_cast<const float*>(x), static_cast<const float*>(w_gate), bias,
-                           logits_ws, counts, T, d, E);
-    }
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(softmax_topk_kernel,
-                       dim3((T + kRouteTokensPerBlock - 1) / kRouteTokensPerBlock), dim3(256), 0, st,
-                       logits_ws, idx, gate, margin, counts, T, E, s.k, s.renormalize);
-    err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(route_finalize_kernel, dim3(1), dim3(1024), 0, st, counts, offsets, hot_mask, E, H);
-    return hipGetLastError();
+    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, nullptr, 16,
+                                st);
 }
 
 }  // namespace moe

@@ -56,6 +56,8 @@ EXTRA = {
                                renormalize=True, seed=15, gate_std=0.3),
     "many_experts": wl.MoEConfig("many_experts", T=600, d_model=64, d_ff=64, E=300, k=2, dtype="bf16",
                                  renormalize=True, seed=16, gate_std=0.5),
+    "max_experts": wl.MoEConfig("max_experts", T=50, d_model=32, d_ff=32, E=1024, k=8, dtype="bf16",
+                                renormalize=True, seed=18, gate_std=0.5),
     "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
                                renormalize=False, seed=17, zipf_s=40.0),
     "switch_large_skew_matched": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
@@ -67,7 +69,7 @@ def CFG(name):
 
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
-         "many_experts", "all_to_one"]
+         "many_experts", "max_experts", "all_to_one"]
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched"]
 LARGE = ["nllb_decode", "nllb_prefill_skew"]
 
