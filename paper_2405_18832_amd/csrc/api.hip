@@ -114,7 +114,7 @@ moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void
     if (st != MOE_OK) return st;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, offsets, mask, y_perm, at<void>(ws, L.h),
-                                      at<Tile>(ws, L.tiles), at<int32_t>(ws, L.ntiles),
+                                      at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big), at<int32_t>(ws, L.ntiles),
                                       static_cast<hipStream_t>(stream)));
 }
 
@@ -154,8 +154,8 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     // tile list; the chunks place their assignments; the first product gathers token rows through tokmap.
     int32_t* hist = at<int32_t>(ws, L.hist);
     int32_t* tokmap = at<int32_t>(ws, L.tokmap);
-    Tile* tiles = at<Tile>(ws, L.tiles);
-    int32_t* ntiles = at<int32_t>(ws, L.ntiles);
+    const TileLists lists = ffn_tile_lists(*shape, at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big),
+                                           at<int32_t>(ws, L.ntiles));
     hipError_t e;
     int nchunks = 0;
     const int tok = route_chunk_tokens(*shape);
@@ -165,7 +165,7 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
     e = launch_scan_finalize(hist, nchunks, shape->E, cnt, offsets, derive ? H : -1, derive ? own_mask : nullptr,
-                             mask, tiles, ntiles, ffn_tile_rows(*shape), hs);
+                             mask, &lists, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (hot_mask_out != nullptr) {
         e = launch_mask_out(used, hot_mask_out, shape->E, hs);
@@ -174,8 +174,7 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     if (shape->T == 0) return MOE_OK;
     e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
-    e = launch_expert_products(*shape, x, tokmap, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), tiles, ntiles,
-                               hs);
+    e = launch_expert_products(*shape, x, tokmap, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
     return from_hip(e);

@@ -47,11 +47,62 @@ struct Tile {
     int32_t pad;
 };
 
+// Tiles of experts with at least kBigMinRows rows go to the LDS-tiled MFMA kernel (tiles of
+// kBigTileRows rows); smaller experts are weight-streaming work.
+constexpr int kBigTileRows = 256;
+constexpr int kBigMinRows = 128;
+
+struct TileLists {
+    Tile* small_tiles;     // capacity A / small_rows + E
+    Tile* big_tiles;       // capacity A / kBigTileRows + E (unused when big_min == 0)
+    int32_t* ntiles;       // [0] small count, [1] big count
+    int small_rows;        // rows per small tile
+    int big_min;           // experts with >= big_min rows are "big"; 0 = none
+};
+
+#ifdef __HIPCC__
+// Called by all 1024 threads of a block, thread e owning expert e (row0, m rows; m = 0 when the
+// expert is empty or masked out).  `scan` is an LDS array of MOE_MAX_E ints.
+__device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLists tl, int32_t* scan) {
+    const bool big = tl.big_min > 0 && m >= tl.big_min;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int rows = pass == 0 ? tl.small_rows : kBigTileRows;
+        const bool mine = (pass == 1) == big;
+        const int nt = mine ? (m + rows - 1) / rows : 0;
+        __syncthreads();
+        scan[e] = nt;
+        __syncthreads();
+        for (int s = 1; s < MOE_MAX_E; s <<= 1) {
+            const int add = (e >= s) ? scan[e - s] : 0;
+            __syncthreads();
+            scan[e] += add;
+            __syncthreads();
+        }
+        Tile* out = pass == 0 ? tl.small_tiles : tl.big_tiles;
+        const int base = scan[e] - nt;
+        for (int i = 0; i < nt; ++i) {
+            Tile t;
+            t.expert = e;
+            t.row0 = row0 + i * rows;
+            t.rows = min(rows, m - i * rows);
+            t.pad = 0;
+            out[base + i] = t;
+        }
+        if (e == MOE_MAX_E - 1) tl.ntiles[pass] = scan[e];
+        if (tl.big_min <= 0 && pass == 0) {      // no large experts possible
+            if (e == 0) tl.ntiles[1] = 0;
+            break;
+        }
+    }
+}
+#endif
+
 // ---- workspace ----------------------------------------------------------------
 struct WsLayout {
     size_t hist;       // int32 [ceil(T/16), E]  chunk histograms / slot bases of the counting sort
-    size_t ntiles;     // int32 [64]  (element 0 used)
-    size_t tiles;      // Tile [A/16 + E + 1]
+    size_t ntiles;     // int32 [64]  ([0] = tiles of small experts, [1] = tiles of large experts)
+    size_t tiles;      // Tile [A/16 + E + 1]   row tiles of the weight-streaming kernel
+    size_t tiles_big;  // Tile [A/256 + E + 1]  row tiles of the LDS-tiled kernel
     size_t h;          // dtype [A, f]
     size_t idx;        // int32 [A]         -- the rest is used by moe_layer_forward only
     size_t gate;       // float [A]
@@ -81,6 +132,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.hist = take(((static_cast<size_t>(s.T) + 15) / 16 + 1) * E * 4);
     L.ntiles = take(64 * 4);
     L.tiles = take((A / 16 + E + 1) * sizeof(Tile));
+    L.tiles_big = take((A / 256 + E + 1) * sizeof(Tile));
     L.h = take(A * s.d_ff * es);
     L.idx = take(A * 4);
     L.gate = take(A * 4);
@@ -104,20 +156,23 @@ int route_chunk_tokens(const moe_shape& s);
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
-                                uint8_t* hot_mask, const uint8_t* mask_in, Tile* tiles, int32_t* ntiles,
-                                int tile_rows, hipStream_t st);
+                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st);
+TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws);
 hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
 int ffn_tile_rows(const moe_shape& s);
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
-                                  const void* w2, float* y_perm, void* h_ws, const Tile* tiles,
-                                  const int32_t* ntiles, hipStream_t st);
+                                  const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
+                                  hipStream_t st);
+hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
+                               void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
+                               hipStream_t st);
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
                           int32_t* hist_ws, hipStream_t st);
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm,
-                             void* h_ws, Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st);
+                             void* h_ws, Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, hipStream_t st);
 hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t* inv_perm,
                           const int32_t* idx, const float* gate, const uint8_t* mask, void* out,
                           hipStream_t st);

@@ -50,14 +50,12 @@ hipError_t launch_pack(const moe_shape& s, int which, const void* src, void* dst
 }
 
 // ---------------------------------------------------------------------------
-// tile list: every active expert's row segment cut into tiles of `tile_rows` rows.
-// One block, one thread per expert, exclusive scan of the tile counts in LDS.
+// tile lists from caller-supplied offsets (the stand-alone expert-FFN call): every active,
+// masked-in expert's row segment cut into row tiles.  One block, one thread per expert.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __restrict__ offsets,
-                                                           const uint8_t* __restrict__ mask,
-                                                           Tile* __restrict__ tiles,
-                                                           int32_t* __restrict__ ntiles, int E, int A,
-                                                           int tile_rows) {
+                                                           const uint8_t* __restrict__ mask, int E, int A,
+                                                           const TileLists lists) {
     __shared__ int32_t scan[MOE_MAX_E];
     const int e = threadIdx.x;
     int row0 = 0, m = 0;
@@ -66,25 +64,7 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
         m = offsets[e + 1] - row0;
         if (row0 < 0 || m < 0 || row0 + m > A) m = 0;   // offsets that are not prefix sums: run nothing
     }
-    const int nt = (m + tile_rows - 1) / tile_rows;
-    scan[e] = nt;
-    __syncthreads();
-    for (int s = 1; s < MOE_MAX_E; s <<= 1) {
-        const int add = (e >= s) ? scan[e - s] : 0;
-        __syncthreads();
-        scan[e] += add;
-        __syncthreads();
-    }
-    const int base = scan[e] - nt;
-    for (int i = 0; i < nt; ++i) {
-        Tile t;
-        t.expert = e;
-        t.row0 = row0 + i * tile_rows;
-        t.rows = min(tile_rows, m - i * tile_rows);
-        t.pad = 0;
-        tiles[base + i] = t;
-    }
-    if (e == MOE_MAX_E - 1) ntiles[0] = scan[e];
+    emit_tiles(e, row0, m, lists, scan);
 }
 
 // ---------------------------------------------------------------------------
@@ -98,11 +78,163 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 // the same rows).  A wavefront owns 4 n-blocks (64 output columns) x up to TFMAX*16 token rows
 // over one k-slice; the KSPLIT wavefronts that share an output tile add their partial sums in
 // LDS in a fixed order.  Blocks are persistent and stride over (tile, n-group) units, whose
-// number is only known on the device.  PF k-steps of loads are kept in flight per wavefront.
+// number is only known on the device.
+//
+// The inner loop is specialised on the exact number of token fragments of the tile (TFC), so
+// every k-step issues a fixed number of loads: the compiler can then count outstanding loads
+// exactly and keeps PF k-steps in flight across loop iterations (with a data-dependent number
+// of loads it drains the queue on every iteration).
 // With `rowmap`, row p of the activations is read from act[rowmap[p]] (the token gather of the
 // dispatch step folded into the first product); output rows are always in permuted order.
 // ---------------------------------------------------------------------------
-template <int TFMAX, int KSPLIT, int PF, bool FIRST>
+// tuning constants (overridable at build time)
+#ifndef MOE_PF_TF1
+#define MOE_PF_TF1 6      // k-steps of loads in flight per wavefront, tiles of <= 16 rows
+#endif
+#ifndef MOE_PF_TF2
+#define MOE_PF_TF2 4      // ... tiles of <= 32 rows
+#endif
+#ifndef MOE_PF_TF3
+#define MOE_PF_TF3 3      // ... tiles of <= 48 rows
+#endif
+#ifndef MOE_PF_TF4
+#define MOE_PF_TF4 3      // ... tiles of <= 64 rows
+#endif
+#ifndef MOE_KS4_STEPS
+#define MOE_KS4_STEPS 96  // split K over 4 wavefronts from this many k-steps on
+#endif
+#ifndef MOE_KS2_STEPS
+#define MOE_KS2_STEPS 48  // split K over 2 wavefronts from this many k-steps on
+#endif
+#ifndef MOE_BALANCE_GRID
+#define MOE_BALANCE_GRID 0
+#endif
+
+template <int TFC> struct StreamPF;
+template <> struct StreamPF<1> { static constexpr int value = MOE_PF_TF1; };
+template <> struct StreamPF<2> { static constexpr int value = MOE_PF_TF2; };
+template <> struct StreamPF<3> { static constexpr int value = MOE_PF_TF3; };
+template <> struct StreamPF<4> { static constexpr int value = MOE_PF_TF4; };
+
+// One wavefront's share of one unit: 4 n-blocks x TFC token fragments over k-steps [kb0, kb1).
+template <int TFC, int TFMAX, int KSPLIT, bool FIRST>
+__device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
+                                            const int32_t* __restrict__ rowmap,
+                                            const uint16_t* __restrict__ wpk, void* __restrict__ outp,
+                                            const Tile tl, const int ng, const bool active, const int N,
+                                            const int K, const int kb0, const int kb1, f32x4* red) {
+    constexpr int PF = StreamPF<TFC>::value;
+    constexpr int NGB = 4 / KSPLIT;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int ks = wave % KSPLIT, ngs = wave / KSPLIT;
+    const int nblk = N >> 4, kblk = K >> 5;
+    f32x4 acc[4][TFC];
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+        for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (active && kb0 < kb1) {
+        const uint16_t* wp[4];
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf) {
+            const int nb = min(ng * 4 + nf, nblk - 1);
+            wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
+        }
+        const uint16_t* ap[TFC];
+#pragma unroll
+        for (int tf = 0; tf < TFC; ++tf) {
+            int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+            if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
+            ap[tf] = act + static_cast<size_t>(row) * K + g * 8;
+        }
+        bf16x8 a[PF][4], b[PF][TFC];
+        auto issue = [&](int slot, int kb) {
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf)
+                a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
+#pragma unroll
+            for (int tf = 0; tf < TFC; ++tf) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * 32);
+        };
+        auto fma = [&](int slot) {
+#pragma unroll
+            for (int tf = 0; tf < TFC; ++tf)
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+                    acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[slot][tf], acc[nf][tf], 0, 0, 0);
+        };
+        // prologue: always PF steps of loads (past the end the last step is re-read, never used)
+#pragma unroll
+        for (int p = 0; p < PF; ++p) issue(p, min(kb0 + p, kb1 - 1));
+        int kb = kb0;
+        for (; kb + 2 * PF <= kb1; kb += PF) {            // steady state: fixed number of loads per step
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                fma(p);
+                issue(p, kb + p + PF);
+            }
+        }
+        if (kb + PF < kb1) {                               // one partial round of refills
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                fma(p);
+                issue(p, min(kb + p + PF, kb1 - 1));
+            }
+            kb += PF;
+        }
+#pragma unroll
+        for (int p = 0; p < PF; ++p)                       // drain: no more loads
+            if (kb + p < kb1) fma(p);
+    }
+
+    if (KSPLIT > 1) {
+        if (active && ks > 0) {
+            f32x4* dst = red + (static_cast<size_t>((ks - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+                for (int tf = 0; tf < TFC; ++tf) dst[(nf * TFMAX + tf) * 64] = acc[nf][tf];
+        }
+        __syncthreads();
+        if (active && ks == 0) {
+#pragma unroll
+            for (int s = 1; s < KSPLIT; ++s) {
+                const f32x4* src = red + (static_cast<size_t>((s - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+                    for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] += src[(nf * TFMAX + tf) * 64];
+            }
+        }
+    }
+    if (active && ks == 0) {
+#pragma unroll
+        for (int tf = 0; tf < TFC; ++tf) {
+            const int lr = tf * 16 + r;
+            if (lr >= tl.rows) continue;
+            const size_t rowoff = static_cast<size_t>(tl.row0 + lr) * N;
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf) {
+                const int nb = ng * 4 + nf;
+                if (nb >= nblk) continue;
+                const int n = nb * 16 + g * 4;
+                const f32x4 v = acc[nf][tf];
+                if (FIRST) {
+                    uint2 pk;
+                    pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
+                    pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + rowoff + n) = pk;
+                } else {
+                    *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + rowoff + n) = v;
+                }
+            }
+        }
+    }
+    if (KSPLIT > 1) __syncthreads();
+}
+
+template <int TFMAX, int KSPLIT, bool FIRST>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
                                                          const int32_t* __restrict__ rowmap,
                                                          const uint16_t* __restrict__ wpk,
@@ -112,8 +244,7 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K) {
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int r = lane & 15, g = lane >> 4;
+    const int wave = threadIdx.x >> 6;
     const int ks = wave % KSPLIT, ngs = wave / KSPLIT;
     const int nblk = N >> 4, kblk = K >> 5;
     const int ngroups = (nblk + 3) >> 2;
@@ -121,118 +252,27 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
     const int kb_per = (kblk + KSPLIT - 1) / KSPLIT;
     const int kb0 = min(kblk, ks * kb_per), kb1 = min(kblk, kb0 + kb_per);
     const int nbu = ntiles_p[0] * ngchunks;
-
-    for (int bu = blockIdx.x; bu < nbu; bu += gridDim.x) {
+    int stride = gridDim.x;
+#if MOE_BALANCE_GRID
+    {   // use only as many blocks as make every block run the same number of units
+        const int rounds = (nbu + stride - 1) / stride;
+        if (rounds > 0) stride = (nbu + rounds - 1) / rounds;
+    }
+    if (static_cast<int>(blockIdx.x) >= stride) return;
+#endif
+    for (int bu = blockIdx.x; bu < nbu; bu += stride) {
         const Tile tl = tiles[bu / ngchunks];
         const int ng = (bu % ngchunks) * NGB + ngs;
         const bool active = ng < ngroups;                 // wave-uniform
-        const int tfc = (tl.rows + 15) >> 4;              // token fragments in use, 1..TFMAX
-        f32x4 acc[4][TFMAX];
-#pragma unroll
-        for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-            for (int tf = 0; tf < TFMAX; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        if (active) {
-            const uint16_t* wp[4];
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf) {
-                const int nb = min(ng * 4 + nf, nblk - 1);
-                wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
-            }
-            const uint16_t* ap[TFMAX];
-#pragma unroll
-            for (int tf = 0; tf < TFMAX; ++tf) {
-                int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
-                if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
-                ap[tf] = act + static_cast<size_t>(row) * K + g * 8;
-            }
-            bf16x8 a[PF][4], b[PF][TFMAX];
-            auto issue = [&](int slot, int kb) {
-#pragma unroll
-                for (int nf = 0; nf < 4; ++nf)
-                    a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
-#pragma unroll
-                for (int tf = 0; tf < TFMAX; ++tf)
-                    if (tf < tfc) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * 32);
-            };
-            auto fma = [&](int slot) {
-#pragma unroll
-                for (int tf = 0; tf < TFMAX; ++tf)
-                    if (tf < tfc) {
-#pragma unroll
-                        for (int nf = 0; nf < 4; ++nf)
-                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[slot][tf],
-                                                                                  acc[nf][tf], 0, 0, 0);
-                    }
-            };
-#pragma unroll
-            for (int p = 0; p < PF; ++p)
-                if (kb0 + p < kb1) issue(p, kb0 + p);
-            int kb = kb0;
-            for (; kb + 2 * PF <= kb1; kb += PF) {        // steady state: no bounds checks
-#pragma unroll
-                for (int p = 0; p < PF; ++p) {
-                    fma(p);
-                    issue(p, kb + p + PF);
-                }
-            }
-            for (; kb < kb1; kb += PF) {                  // drain
-#pragma unroll
-                for (int p = 0; p < PF; ++p)
-                    if (kb + p < kb1) {
-                        fma(p);
-                        if (kb + p + PF < kb1) issue(p, kb + p + PF);
-                    }
-            }
-        }
-
-        if (KSPLIT > 1) {
-            if (active && ks > 0) {
-                f32x4* dst = red + (static_cast<size_t>((ks - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
-#pragma unroll
-                for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-                    for (int tf = 0; tf < TFMAX; ++tf)
-                        if (tf < tfc) dst[(nf * TFMAX + tf) * 64] = acc[nf][tf];
-            }
-            __syncthreads();
-            if (active && ks == 0) {
-#pragma unroll
-                for (int s = 1; s < KSPLIT; ++s) {
-                    const f32x4* src = red + (static_cast<size_t>((s - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
-#pragma unroll
-                    for (int nf = 0; nf < 4; ++nf)
-#pragma unroll
-                        for (int tf = 0; tf < TFMAX; ++tf)
-                            if (tf < tfc) acc[nf][tf] += src[(nf * TFMAX + tf) * 64];
-                }
-            }
-        }
-        if (active && ks == 0) {
-#pragma unroll
-            for (int tf = 0; tf < TFMAX; ++tf) {
-                const int lr = tf * 16 + r;
-                if (lr >= tl.rows) continue;
-                const size_t rowoff = static_cast<size_t>(tl.row0 + lr) * N;
-#pragma unroll
-                for (int nf = 0; nf < 4; ++nf) {
-                    const int nb = ng * 4 + nf;
-                    if (nb >= nblk) continue;
-                    const int n = nb * 16 + g * 4;
-                    const f32x4 v = acc[nf][tf];
-                    if (FIRST) {
-                        uint2 pk;
-                        pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
-                        pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
-                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + rowoff + n) = pk;
-                    } else {
-                        *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + rowoff + n) = v;
-                    }
-                }
-            }
-        }
-        if (KSPLIT > 1) __syncthreads();
+        const int tfc = (tl.rows + 15) >> 4;              // token fragments in use: block-uniform
+        if (TFMAX >= 4 && tfc == 4)
+            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+        else if (TFMAX >= 4 && tfc == 3)
+            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+        else if (TFMAX >= 2 && tfc == 2)
+            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+        else
+            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
     }
 }
 
@@ -279,11 +319,11 @@ int device_cu_count() {
     return cus[dev];
 }
 
-template <int TFMAX, int KSPLIT, int PF, bool FIRST>
+template <int TFMAX, int KSPLIT, bool FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
                                 hipStream_t st) {
-    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, PF, FIRST>;
+    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
         int n = 0;
@@ -298,25 +338,25 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     return hipGetLastError();
 }
 
-template <int TFMAX, int PF, bool FIRST>
+template <int TFMAX, bool FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
                                   long max_tiles, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
-        return launch_stream<TFMAX, 4, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
+        return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
     if (ksplit == 2)
-        return launch_stream<TFMAX, 2, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+        return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
                                                   max_tiles * ((ngroups + 1) / 2), st);
-    return launch_stream<TFMAX, 1, PF, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+    return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
                                               max_tiles * ((ngroups + 3) / 4), st);
 }
 
 // k-steps of 32 per wavefront: split K over up to 4 wavefronts while each keeps >= 24 steps
 static int pick_ksplit(int K) {
     const int steps = K / 32;
-    if (steps >= 96) return 4;
-    if (steps >= 48) return 2;
+    if (steps >= MOE_KS4_STEPS) return 4;
+    if (steps >= MOE_KS2_STEPS) return 2;
     return 1;
 }
 
@@ -338,13 +378,27 @@ static int ffn_tfmax(const moe_shape& s) { return s.T <= 16 ? 1 : (s.T <= 32 ? 2
 
 int ffn_tile_rows(const moe_shape& s) { return s.dtype == MOE_BF16 ? 16 * ffn_tfmax(s) : 16; }
 
-// the two grouped products over an existing tile list
+TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws) {
+    TileLists l;
+    l.small_tiles = small_ws;
+    l.big_tiles = big_ws;
+    l.ntiles = ntiles_ws;
+    l.small_rows = ffn_tile_rows(s);
+    // a large expert needs kBigMinRows rows, and an expert holds at most T rows
+    l.big_min = (s.dtype == MOE_BF16 && s.T >= kBigMinRows) ? kBigMinRows : 0;
+    return l;
+}
+
+// the two grouped products over existing tile lists
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
-                                  const void* w2, float* y_perm, void* h_ws, const Tile* tiles,
-                                  const int32_t* ntiles, hipStream_t st) {
+                                  const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
+                                  hipStream_t st) {
     const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
-    const int tile_rows = ffn_tile_rows(s);
+    const int tile_rows = lists.small_rows;
+    const Tile* tiles = lists.small_tiles;
+    const int32_t* ntiles = lists.ntiles;
     const long max_tiles = A / tile_rows + (E < A ? E : A);
+    const long max_big = lists.big_min > 0 ? A / kBigTileRows + (E < A / lists.big_min ? E : A / lists.big_min) : 0;
     hipError_t err;
     if ((err = mark(0, st)) != hipSuccess) return err;
 
@@ -371,29 +425,37 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     uint16_t* h = static_cast<uint16_t*>(h_ws);
     const int ks1 = pick_ksplit(d), ks2 = pick_ksplit(f);
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, 4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, 4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
-        default: err = launch_stream_k<4, 3, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
+    if (max_big > 0) {
+        err = launch_tile_product(true, xp, rowmap, p1, h, lists.big_tiles, ntiles + 1, f, d, max_big, st);
+        if (err != hipSuccess) return err;
+    }
     if ((err = mark(1, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, 4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, 4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
-        default: err = launch_stream_k<4, 3, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
+    if (max_big > 0) {
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, lists.big_tiles, ntiles + 1, d, f, max_big, st);
+        if (err != hipSuccess) return err;
+    }
     return mark(2, st);
 }
 
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
-                             Tile* tiles_ws, int32_t* ntiles_ws, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, tiles_ws, ntiles_ws, s.E,
-                       s.T * s.k, ffn_tile_rows(s));
+                             Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, hipStream_t st) {
+    const TileLists lists = ffn_tile_lists(s, tiles_ws, tiles_big_ws, ntiles_ws);
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, s.E, s.T * s.k, lists);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    return launch_expert_products(s, x_perm, nullptr, w1, w2, y_perm, h_ws, tiles_ws, ntiles_ws, st);
+    return launch_expert_products(s, x_perm, nullptr, w1, w2, y_perm, h_ws, lists, st);
 }
 
 }  // namespace moe

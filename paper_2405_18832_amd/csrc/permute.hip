@@ -129,7 +129,7 @@ hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                        nchunks);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    err = launch_scan_finalize(hist_ws, nchunks, E, nullptr, nullptr, -1, nullptr, nullptr, nullptr, nullptr, 16, st);
+    err = launch_scan_finalize(hist_ws, nchunks, E, nullptr, nullptr, -1, nullptr, nullptr, nullptr, st);
     if (err != hipSuccess) return err;
     err = launch_place(s, idx, offsets, hist_ws, perm, inv_perm, nullptr, kPermChunk, st);
     if (err != hipSuccess) return err;

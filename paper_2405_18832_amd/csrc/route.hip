@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void route_fused_kernel(const ST* __restrict__
 //           place (the slot bases of the counting sort); the total is the expert's token count.
 //  phase 2: prefix sums over experts -> offsets; top-H hot mask (rank by count, ties by lowest
 //           index); the tile list of the expert FFN (every active, masked-in expert's segment
-//           cut into tiles of `tile_rows` rows).
+//           cut into row tiles: one list for small experts, one for large ones).
 // Any output pointer may be NULL.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
@@ -205,8 +205,7 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
                                                              int32_t* __restrict__ offsets, int H,
                                                              uint8_t* __restrict__ hot_mask,
                                                              const uint8_t* __restrict__ mask_in,
-                                                             Tile* __restrict__ tiles, int32_t* __restrict__ ntiles,
-                                                             int tile_rows) {
+                                                             const TileLists lists, const int want_tiles) {
     __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -252,28 +251,8 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     } else if (mask_in != nullptr && e < E) {
         on = mask_in[e] != 0;
     }
-    if (tiles == nullptr) return;      // uniform: every thread sees the same pointer
-    __syncthreads();
-    const int m = on ? mine : 0;
-    const int nt = (m + tile_rows - 1) / tile_rows;
-    scan[e] = nt;
-    __syncthreads();
-    for (int s = 1; s < MOE_MAX_E; s <<= 1) {
-        const int add = (e >= s) ? scan[e - s] : 0;
-        __syncthreads();
-        scan[e] += add;
-        __syncthreads();
-    }
-    const int base = scan[e] - nt;
-    for (int i = 0; i < nt; ++i) {
-        Tile t;
-        t.expert = e;
-        t.row0 = row0 + i * tile_rows;
-        t.rows = min(tile_rows, m - i * tile_rows);
-        t.pad = 0;
-        tiles[base + i] = t;
-    }
-    if (e == MOE_MAX_E - 1) ntiles[0] = scan[e];
+    if (!want_tiles) return;           // uniform: a kernel argument
+    emit_tiles(e, row0, on ? mine : 0, lists, scan);
 }
 
 __global__ void mask_out_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int E) {
@@ -327,10 +306,10 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
 }
 
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
-                                uint8_t* hot_mask, const uint8_t* mask_in, Tile* tiles, int32_t* ntiles,
-                                int tile_rows, hipStream_t st) {
+                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st) {
+    const TileLists none{nullptr, nullptr, nullptr, 16, 0};
     hipLaunchKernelGGL(scan_finalize_kernel, dim3(1), dim3(1024), 0, st, chunk_hist, nchunks, E, counts, offsets, H,
-                       hot_mask, mask_in, tiles, ntiles, tile_rows);
+                       hot_mask, mask_in, lists ? *lists : none, lists ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -345,8 +324,7 @@ hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, c
         hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, st);
         if (err != hipSuccess) return err;
     }
-    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, nullptr, 16,
-                                st);
+    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, st);
 }
 
 }  // namespace moe
