@@ -4,8 +4,8 @@
 //
 //   out[row, n] = sum_k act[row, k] * W_e[n, k]          (FIRST: relu, rounded to bf16)
 //
-// Block = 8 wavefronts on a 256 (rows) x 256 (columns) output tile, K in steps of 64 through
-// double-buffered LDS.  Both operands sit in LDS in MFMA-fragment order (16 x 32 fragments of
+// Block = 8 wavefronts on a 256 (rows) x 256 (columns) output tile, K in steps of 32 through a
+// ring of four LDS stages (the copies of three stages are in flight while one is consumed).  Both operands sit in LDS in MFMA-fragment order (16 x 32 fragments of
 // 1 KiB, one 16-byte piece per lane), so every LDS read of the inner loop is a conflict-free
 // 1 KiB wavefront read.  Global memory is copied straight into LDS (16 bytes per lane, no
 // registers in between): the packed weights are already in fragment order in HBM, and for the
@@ -20,8 +20,10 @@ namespace moe {
 
 constexpr int kTM = kBigTileRows;   // 256 rows
 constexpr int kTN = 256;            // columns
-constexpr int kTK = 64;             // k per LDS stage
-constexpr int kStageBytes = kTM * kTK * 2;          // 32 KiB per operand per stage
+constexpr int kTK = 32;             // k per LDS stage
+constexpr int kStages = 4;          // ring of LDS stages: one being consumed, up to three in flight
+constexpr int kOperandBytes = kTM * kTK * 2;        // 16 KiB per operand per stage
+constexpr int kStageBytes = 2 * kOperandBytes;      // 32 KiB per stage
 
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
@@ -31,6 +33,37 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, unsigned char* ld
     __builtin_amdgcn_global_load_lds((gptr_t)(src), (lptr_t)(lds_base), 16, 0, 0);
 }
 
+// One 32-k LDS stage of the inner product for one wavefront: 4 weight fragments x 8 row fragments.
+// `wbase` / `xbase` point at this lane's 16 bytes of the wavefront's first weight / row fragment;
+// the next fragment lies 1 KiB further.  LDS reads run one pair of row fragments ahead of the MFMAs
+// that consume them.
+__device__ __forceinline__ void tile_stage(const unsigned char* __restrict__ wbase,
+                                           const unsigned char* __restrict__ xbase, f32x4 (&acc)[4][8]) {
+    bf16x8 w[4], x0, x1, y0, y1;
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf) w[nf] = *reinterpret_cast<const bf16x8*>(wbase + nf * 1024);
+    x0 = *reinterpret_cast<const bf16x8*>(xbase);
+    x1 = *reinterpret_cast<const bf16x8*>(xbase + 1024);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        if (p + 1 < 4) {                                   // reads for the next pair go out first
+            y0 = *reinterpret_cast<const bf16x8*>(xbase + (2 * p + 2) * 1024);
+            y1 = *reinterpret_cast<const bf16x8*>(xbase + (2 * p + 3) * 1024);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf) {
+            acc[nf][2 * p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x0, acc[nf][2 * p], 0, 0, 0);
+            acc[nf][2 * p + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x1, acc[nf][2 * p + 1], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (p + 1 < 4) {
+            x0 = y0;
+            x1 = y1;
+        }
+    }
+}
+
 template <bool FIRST>
 __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restrict__ act,
                                                        const int32_t* __restrict__ rowmap,
@@ -38,25 +71,46 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        void* __restrict__ outp, const Tile* __restrict__ tiles,
                                                        const int32_t* __restrict__ ntiles_p, int N, int K) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // stage st: 32 activation fragments at smem + st * 2 * kStageBytes, 32 weight fragments behind them;
-    // fragment (block b of 16 rows/columns, kb) of a stage sits at ((b * 2 + kb) * 1024) bytes
-    auto As = [&](int st) { return smem + st * 2 * kStageBytes; };
-    auto Bs = [&](int st) { return smem + st * 2 * kStageBytes + kStageBytes; };
+    // stage st: 16 row fragments at smem + st * kStageBytes, 16 weight fragments behind them
+    auto As = [&](int st) { return smem + st * kStageBytes; };
+    auto Bs = [&](int st) { return smem + st * kStageBytes + kOperandBytes; };
 
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int wm = wave >> 2, wn = wave & 3;
     const int r = lane & 15, g = lane >> 4;
     const int nblk = N >> 4, kblk = K >> 5;
     const int ntn = (N + kTN - 1) / kTN;
-    const int nkt = (kblk + 1) >> 1;                    // k stages of 64
-    const int total = ntiles_p[0] * ntn;
+    const int ntiles = ntiles_p[0];
 
-    for (int u = blockIdx.x; u < total; u += gridDim.x) {
-        const Tile tl = tiles[u / ntn];
-        const int nt = u % ntn;
-        // This wavefront stages fragments 4*wave .. 4*wave+3 of each operand: blocks 2*wave and 2*wave+1,
-        // both 32-k halves.  A lane fetches the 16 bytes that belong at its own slot of the fragment:
-        // row (lane % 16) of the block, k-group (lane / 16).
+    // Unit order.  Blocks are handed to the 8 XCDs round-robin, and each XCD has its own L2.  The blocks
+    // of one XCD therefore work, at any time, on a compact GM x GN patch of (row tile, column tile) space,
+    // so that its L2 serves every activation panel GN times and every weight panel GM times; the 8 XCDs
+    // take 8 patches of the same column group (same weight panels, served to the others by the
+    // last-level cache).  Falls back to row-major order when the grid does not split that way.
+    const int G = gridDim.x;
+    const int GN = min(ntn, 8);
+    const bool patches = (G % 8 == 0) && ((G / 8) % GN == 0);
+    const int S = patches ? G / 8 : 1;
+    const int GM = patches ? S / GN : 1;
+    const int nrg = (ntiles + GM - 1) / GM, ncg = (ntn + GN - 1) / GN;
+    const int ngroups = nrg * ncg;
+    const int total = patches ? ((ngroups + 7) / 8) * G : ntiles * ntn;
+
+    for (int L = blockIdx.x; L < total; L += G) {
+        int mt, nt;
+        if (patches) {
+            const int grp = (L / G) * 8 + (blockIdx.x & 7), slot = blockIdx.x >> 3;
+            if (grp >= ngroups) continue;
+            mt = (grp % nrg) * GM + slot / GN;
+            nt = (grp / nrg) * GN + slot % GN;
+            if (mt >= ntiles || nt >= ntn) continue;
+        } else {
+            mt = L / ntn;
+            nt = L % ntn;
+        }
+        const Tile tl = tiles[mt];
+        // This wavefront stages fragments 2*wave and 2*wave+1 of each operand.  A lane fetches the 16
+        // bytes that belong at its own slot of the fragment: row (lane % 16), k-group (lane / 16).
         const uint16_t* arow[2];
         const uint16_t* brow[2];
 #pragma unroll
@@ -74,47 +128,30 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        auto stage_in = [&](int st, int kt) {
-            const int nk32 = min(2, kblk - 2 * kt);          // the last stage may hold one 32-k half only
+        auto stage_in = [&](int st, int kb) {              // 4 copies per wavefront and stage
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-                    if (kb < nk32) {
-                        copy16_to_lds(arow[i] + kt * 64 + kb * 32, As(st) + ((2 * wave + i) * 2 + kb) * 1024);
-                        copy16_to_lds(brow[i] + (static_cast<size_t>(2 * kt + kb)) * 512,
-                                      Bs(st) + ((2 * wave + i) * 2 + kb) * 1024);
-                    }
-        };
-        auto compute = [&](int st, int nk32) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                if (kb < nk32) {
-                    bf16x8 w[4];
-#pragma unroll
-                    for (int nf = 0; nf < 4; ++nf)
-                        w[nf] = *reinterpret_cast<const bf16x8*>(Bs(st) + (((wn * 4 + nf) * 2 + kb) * 64 + lane) * 16);
-#pragma unroll
-                    for (int tf = 0; tf < 8; ++tf) {
-                        const bf16x8 x =
-                            *reinterpret_cast<const bf16x8*>(As(st) + (((wm * 8 + tf) * 2 + kb) * 64 + lane) * 16);
-#pragma unroll
-                        for (int nf = 0; nf < 4; ++nf)
-                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x, acc[nf][tf], 0, 0, 0);
-                    }
-                }
+            for (int i = 0; i < 2; ++i) {
+                copy16_to_lds(arow[i] + kb * 32, As(st) + (2 * wave + i) * 1024);
+                copy16_to_lds(brow[i] + static_cast<size_t>(kb) * 512, Bs(st) + (2 * wave + i) * 1024);
             }
         };
 
+        const int wave_w = (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
         __syncthreads();                 // every wavefront is done reading the previous unit's stages
-        stage_in(0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's copies have landed in LDS
-        __syncthreads();
-        for (int kt = 0; kt < nkt; ++kt) {
-            if (kt + 1 < nkt) stage_in((kt + 1) & 1, kt + 1);     // in flight while this stage is consumed
-            compute(kt & 1, min(2, kblk - 2 * kt));
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
+#pragma unroll
+        for (int sidx = 0; sidx < kStages - 1; ++sidx)
+            if (sidx < kblk) stage_in(sidx, sidx);
+        for (int kb = 0; kb < kblk; ++kb) {
+            // stage kb must have landed; the copies of up to two later stages (4 each) may stay in flight
+            const int later = min(kStages - 2, kblk - 1 - kb);
+            if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+            else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F74);     // vmcnt(4)
+            else __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
+            // ... for every wavefront, and nobody still reads stage kb-1.  A bare barrier: __syncthreads()
+            // would first drain every outstanding copy (its fence waits for vmcnt(0)) and empty the ring.
+            asm volatile("s_barrier" ::: "memory");
+            if (kb + kStages - 1 < kblk) stage_in((kb + kStages - 1) % kStages, kb + kStages - 1);
+            tile_stage(Bs(kb % kStages) + wave_w, As(kb % kStages) + wave_x, acc);
         }
 
         // epilogue: lane holds 4 consecutive columns of one row per accumulator
@@ -147,7 +184,7 @@ static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const 
                               const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
                               hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
-    constexpr int lds = 4 * kStageBytes;        // 128 KiB: above the default per-block limit
+    constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
     static int per_cu = 0;
     if (per_cu == 0) {
         hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
