@@ -100,15 +100,6 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 #ifndef MOE_PF_TF4
 #define MOE_PF_TF4 3      // ... tiles of <= 64 rows
 #endif
-#ifndef MOE_KS4_STEPS
-#define MOE_KS4_STEPS 96  // split K over 4 wavefronts from this many k-steps on
-#endif
-#ifndef MOE_KS2_STEPS
-#define MOE_KS2_STEPS 48  // split K over 2 wavefronts from this many k-steps on
-#endif
-#ifndef MOE_BALANCE_GRID
-#define MOE_BALANCE_GRID 0
-#endif
 
 template <int TFC> struct StreamPF;
 template <> struct StreamPF<1> { static constexpr int value = MOE_PF_TF1; };
@@ -241,7 +232,7 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          void* __restrict__ outp,
                                                          const Tile* __restrict__ tiles,
                                                          const int32_t* __restrict__ ntiles_p, int N,
-                                                         int K) {
+                                                         int K, int balance) {
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -253,13 +244,14 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
     const int kb0 = min(kblk, ks * kb_per), kb1 = min(kblk, kb0 + kb_per);
     const int nbu = ntiles_p[0] * ngchunks;
     int stride = gridDim.x;
-#if MOE_BALANCE_GRID
-    {   // use only as many blocks as make every block run the same number of units
+    if (balance) {
+        // Units are equal-sized, so a grid that does not divide them ends with a round of few blocks and
+        // little data in flight.  Use only as many blocks as make every block run the same number of
+        // units (the others exit): the memory system sees a constant number of streams to the end.
         const int rounds = (nbu + stride - 1) / stride;
         if (rounds > 0) stride = (nbu + rounds - 1) / rounds;
+        if (static_cast<int>(blockIdx.x) >= stride) return;
     }
-    if (static_cast<int>(blockIdx.x) >= stride) return;
-#endif
     for (int bu = blockIdx.x; bu < nbu; bu += stride) {
         const Tile tl = tiles[bu / ngchunks];
         const int ng = (bu % ngchunks) * NGB + ngs;
@@ -333,8 +325,9 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     long grid = static_cast<long>(device_cu_count()) * per_cu;
     if (grid > max_units) grid = max_units;
     if (grid < 1) grid = 1;
+    // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K);
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -352,11 +345,14 @@ static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t
                                               max_tiles * ((ngroups + 3) / 4), st);
 }
 
-// k-steps of 32 per wavefront: split K over up to 4 wavefronts while each keeps >= 24 steps
-static int pick_ksplit(int K) {
+// Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
+// (>= 16 steps each) for an even spread over the chip; tiles with several row fragments carry more
+// per-unit work and keep >= 24 steps per wavefront.
+static int pick_ksplit(int K, int tfmax) {
     const int steps = K / 32;
-    if (steps >= MOE_KS4_STEPS) return 4;
-    if (steps >= MOE_KS2_STEPS) return 2;
+    const int s4 = tfmax <= 2 ? 64 : 96, s2 = tfmax <= 2 ? 32 : 48;
+    if (steps >= s4) return 4;
+    if (steps >= s2) return 2;
     return 1;
 }
 
@@ -423,7 +419,7 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     const uint16_t* p1 = static_cast<const uint16_t*>(w1);
     const uint16_t* p2 = static_cast<const uint16_t*>(w2);
     uint16_t* h = static_cast<uint16_t*>(h_ws);
-    const int ks1 = pick_ksplit(d), ks2 = pick_ksplit(f);
+    const int ks1 = pick_ksplit(d, ffn_tfmax(s)), ks2 = pick_ksplit(f, ffn_tfmax(s));
     switch (ffn_tfmax(s)) {
         case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
         case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;

@@ -86,87 +86,113 @@ __device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, in
 }
 
 // ---------------------------------------------------------------------------
-// route_fused_kernel<ST, TF>: block = 4 wavefronts, chunk = 16*TF tokens.
+// route_fused_kernel<ST, TF, NW, NF>: block = NW wavefronts, chunk = 16*TF tokens.
 //  bf16: MFMA 16x16x32 with gate rows as the A operand and token rows as the B operand (a lane
-//  ends up with 4 consecutive experts of one token); the 4 wavefronts split the contraction
-//  (each reads its own quarter of every row, so x and the gate matrix cross L1 once per block)
-//  and add their partial logits into LDS one after the other, in wave order.
+//  ends up with 4 consecutive experts of one token).  Experts are taken NF fragments (16*NF
+//  experts) at a time; the NW wavefronts split the contraction (each reads its own slice of
+//  every row, so x and the gate matrix cross L1 once per block) and add their partial logits
+//  into LDS one after the other, in wave order (deterministic).  Every k-step issues exactly
+//  NF + TF loads (rows past the end are clamped, their results dropped), two steps ahead.
 //  fp32: plain FMA dot products, one (token, expert) pair per thread and pass.
+// The chunk's histogram goes to chunk_hist[e * nchunks + chunk].
 // Dynamic LDS: logits [16*TF][E+1] floats, then the histogram [E] ints.
 // ---------------------------------------------------------------------------
-template <typename ST, int TF>
-__global__ __launch_bounds__(256) void route_fused_kernel(const ST* __restrict__ x, const ST* __restrict__ wg,
-                                                          const float* __restrict__ bias,
-                                                          int32_t* __restrict__ topk_idx,
-                                                          float* __restrict__ topk_w, float* __restrict__ margin,
-                                                          int32_t* __restrict__ chunk_hist, int T, int d, int E,
-                                                          int k, int renorm) {
+template <typename ST, int TF, int NW, int NF>
+__global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restrict__ x, const ST* __restrict__ wg,
+                                                              const float* __restrict__ bias,
+                                                              int32_t* __restrict__ topk_idx,
+                                                              float* __restrict__ topk_w,
+                                                              float* __restrict__ margin,
+                                                              int32_t* __restrict__ chunk_hist, int T, int d,
+                                                              int E, int k, int renorm) {
     constexpr int TOK = 16 * TF;
+    constexpr int NT = NW * 64;
     extern __shared__ float lds[];
     const int Ep = E + 1;
     float* L = lds;
     int32_t* hist = reinterpret_cast<int32_t*>(lds + TOK * Ep);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int t0 = blockIdx.x * TOK;
-    for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
+    for (int e = threadIdx.x; e < E; e += NT) hist[e] = 0;
 
     if constexpr (sizeof(ST) == 2) {
         const int r = lane & 15, g = lane >> 4;
         const int ksteps = d >> 5;
-        const int per = (ksteps + 3) >> 2;
+        const int per = (ksteps + NW - 1) / NW;
         const int kb0 = min(ksteps, wave * per), kb1 = min(ksteps, kb0 + per);
         const uint16_t* xrow[TF];
 #pragma unroll
         for (int tf = 0; tf < TF; ++tf)
             xrow[tf] = reinterpret_cast<const uint16_t*>(x) + static_cast<size_t>(min(t0 + tf * 16 + r, T - 1)) * d + g * 8;
-        for (int ec = 0; ec < E; ec += 128) {
-            const int nfr = min(8, (E - ec + 15) >> 4);
-            const uint16_t* wrow[8];
+        for (int ec = 0; ec < E; ec += 16 * NF) {
+            const uint16_t* wrow[NF];
 #pragma unroll
-            for (int nf = 0; nf < 8; ++nf)
+            for (int nf = 0; nf < NF; ++nf)
                 wrow[nf] = reinterpret_cast<const uint16_t*>(wg) + static_cast<size_t>(min(ec + nf * 16 + r, E - 1)) * d + g * 8;
-            f32x4 acc[8][TF];
+            f32x4 acc[NF][TF];
 #pragma unroll
-            for (int nf = 0; nf < 8; ++nf)
+            for (int nf = 0; nf < NF; ++nf)
 #pragma unroll
                 for (int tf = 0; tf < TF; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-            for (int kb = kb0; kb < kb1; ++kb) {
-                bf16x8 b[TF];
+            if (kb0 < kb1) {
+                constexpr int PF = 2;
+                bf16x8 a[PF][NF], b[PF][TF];
+                auto issue = [&](int slot, int kb) {
 #pragma unroll
-                for (int tf = 0; tf < TF; ++tf) b[tf] = *reinterpret_cast<const bf16x8*>(xrow[tf] + kb * 32);
+                    for (int tf = 0; tf < TF; ++tf) b[slot][tf] = *reinterpret_cast<const bf16x8*>(xrow[tf] + kb * 32);
 #pragma unroll
-                for (int nf = 0; nf < 8; ++nf)
-                    if (nf < nfr) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(wrow[nf] + kb * 32);
+                    for (int nf = 0; nf < NF; ++nf) a[slot][nf] = *reinterpret_cast<const bf16x8*>(wrow[nf] + kb * 32);
+                };
+                auto fma = [&](int slot) {
+#pragma unroll
+                    for (int nf = 0; nf < NF; ++nf)
 #pragma unroll
                         for (int tf = 0; tf < TF; ++tf)
-                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[tf], acc[nf][tf], 0, 0, 0);
+                            acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[slot][tf], acc[nf][tf], 0, 0, 0);
+                };
+#pragma unroll
+                for (int p = 0; p < PF; ++p) issue(p, min(kb0 + p, kb1 - 1));
+                int kb = kb0;
+                for (; kb + 2 * PF <= kb1; kb += PF) {
+#pragma unroll
+                    for (int p = 0; p < PF; ++p) {
+                        fma(p);
+                        issue(p, kb + p + PF);
                     }
+                }
+                if (kb + PF < kb1) {
+#pragma unroll
+                    for (int p = 0; p < PF; ++p) {
+                        fma(p);
+                        issue(p, min(kb + p + PF, kb1 - 1));
+                    }
+                    kb += PF;
+                }
+#pragma unroll
+                for (int p = 0; p < PF; ++p)
+                    if (kb + p < kb1) fma(p);
             }
-            for (int w = 0; w < 4; ++w) {        // partial sums are added in wave order: deterministic
+            for (int w = 0; w < NW; ++w) {       // partial sums are added in wave order: deterministic
                 if (wave == w) {
 #pragma unroll
-                    for (int nf = 0; nf < 8; ++nf)
-                        if (nf < nfr) {
+                    for (int nf = 0; nf < NF; ++nf)
 #pragma unroll
-                            for (int tf = 0; tf < TF; ++tf)
+                        for (int tf = 0; tf < TF; ++tf)
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) {
-                                    const int e = ec + nf * 16 + g * 4 + i;
-                                    if (e < E) {
-                                        float* p = L + (tf * 16 + r) * Ep + e;
-                                        const float v = acc[nf][tf][i];
-                                        *p = (w == 0) ? v + (bias ? bias[e] : 0.f) : *p + v;
-                                    }
+                            for (int i = 0; i < 4; ++i) {
+                                const int e = ec + nf * 16 + g * 4 + i;
+                                if (e < E) {
+                                    float* p = L + (tf * 16 + r) * Ep + e;
+                                    const float v = acc[nf][tf][i];
+                                    *p = (w == 0) ? v + (bias ? bias[e] : 0.f) : *p + v;
                                 }
-                        }
+                            }
                 }
                 __syncthreads();
             }
         }
     } else {
-        for (int i = threadIdx.x; i < TOK * E; i += 256) {
+        for (int i = threadIdx.x; i < TOK * E; i += NT) {
             const int tl = i / E, e = i % E;
             const float* xr = reinterpret_cast<const float*>(x) + static_cast<size_t>(min(t0 + tl, T - 1)) * d;
             const float* wr = reinterpret_cast<const float*>(wg) + static_cast<size_t>(e) * d;
@@ -177,10 +203,10 @@ __global__ __launch_bounds__(256) void route_fused_kernel(const ST* __restrict__
         __syncthreads();
     }
 
+    // top-k: 4 tokens per wavefront and pass
     const int grp = lane >> 4, sub = lane & 15;
 #pragma unroll 1
-    for (int pass = 0; pass < TF; ++pass) {
-        const int tl = pass * 16 + wave * 4 + grp;
+    for (int tl = wave * 4 + grp; tl < TOK; tl += NW * 4) {
         const int t = t0 + tl;
         const bool live = t < T;
         const size_t o = static_cast<size_t>(live ? t : 0) * k;
@@ -188,7 +214,8 @@ __global__ __launch_bounds__(256) void route_fused_kernel(const ST* __restrict__
                       margin ? margin + (live ? t : 0) : nullptr, hist);
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
+    const int nchunks = gridDim.x;
+    for (int e = threadIdx.x; e < E; e += NT) chunk_hist[static_cast<size_t>(e) * nchunks + blockIdx.x] = hist[e];
 }
 
 // ---------------------------------------------------------------------------
@@ -209,21 +236,36 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int e = wave; e < E; e += 16) {
-        int carry = 0;
+    // phase 1: wavefront w owns experts w, w+16, ...; it walks them 8 at a time so that the 8 rows'
+    // loads are in flight together (chunk_hist is [E][nchunks]: a row is contiguous)
+    for (int eb = wave; eb < E; eb += 16 * 8) {
+        int carry[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) carry[j] = 0;
         for (int c0 = 0; c0 < nchunks; c0 += 64) {
             const int c = c0 + lane;
-            const int v = (c < nchunks) ? chunk_hist[static_cast<size_t>(c) * E + e] : 0;
-            int incl = v;
+            int v[8];
 #pragma unroll
-            for (int s = 1; s < 64; s <<= 1) {
-                const int o = __shfl_up(incl, s);
-                if (lane >= s) incl += o;
+            for (int j = 0; j < 8; ++j) {
+                const int e = eb + 16 * j;
+                v[j] = (e < E && c < nchunks) ? chunk_hist[static_cast<size_t>(e) * nchunks + c] : 0;
             }
-            if (c < nchunks) chunk_hist[static_cast<size_t>(c) * E + e] = carry + incl - v;
-            carry += __shfl(incl, 63);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int e = eb + 16 * j;
+                int incl = v[j];
+#pragma unroll
+                for (int s = 1; s < 64; s <<= 1) {
+                    const int o = __shfl_up(incl, s);
+                    if (lane >= s) incl += o;
+                }
+                if (e < E && c < nchunks) chunk_hist[static_cast<size_t>(e) * nchunks + c] = carry[j] + incl - v[j];
+                carry[j] += __shfl(incl, 63);
+            }
         }
-        if (lane == 0) cnt[e] = carry;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (lane == 0 && eb + 16 * j < E) cnt[eb + 16 * j] = carry[j];
     }
     __syncthreads();
     const int e = threadIdx.x;
@@ -265,44 +307,61 @@ hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hip
     return hipGetLastError();
 }
 
-int route_chunk_tokens(const moe_shape& s) {
-    return (s.dtype == MOE_BF16 && s.T >= 4096 && s.E <= 128) ? 64 : 16;
+// chunk size (tokens per routing block) and wavefronts per block, from the shape alone
+struct RouteCfg { int tok, nw, nf; };
+static RouteCfg route_cfg(const moe_shape& s) {
+    RouteCfg c{16, 4, 1};
+    if (s.dtype != MOE_BF16) return c;
+    c.nf = s.E >= 113 ? 8 : (s.E >= 49 ? 4 : (s.E >= 17 ? 2 : 1));
+    if (s.T <= 64) { c.tok = 16; c.nw = 16; c.nf = c.nf > 4 ? 4 : c.nf; }   // few blocks: split the contraction 16 ways
+                                                                            // (128 registers per lane: 4 fragments at a time)
+    else if (s.T >= 4096 && s.E <= 256) { c.tok = 32; c.nw = 8; }
+    else { c.tok = 16; c.nw = 8; }
+    return c;
+}
+
+int route_chunk_tokens(const moe_shape& s) { return route_cfg(s).tok; }
+
+template <typename ST, int TF, int NW, int NF>
+static hipError_t launch_route_inst(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                                    int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
+    constexpr int tok = 16 * TF;
+    const unsigned grid = static_cast<unsigned>((s.T + tok - 1) / tok);
+    const size_t lds = static_cast<size_t>(tok) * (s.E + 1) * 4 + static_cast<size_t>(s.E) * 4;
+    auto kern = route_fused_kernel<ST, TF, NW, NF>;
+    if (lds > 48 * 1024) {      // more LDS than the default per-block limit: raise it for this kernel
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (ea != hipSuccess) return ea;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, st, static_cast<const ST*>(x),
+                       static_cast<const ST*>(w_gate), bias, idx, gate, margin, chunk_hist, s.T, s.d_model, s.E, s.k,
+                       s.renormalize);
+    return hipGetLastError();
+}
+
+template <int TF, int NW>
+static hipError_t launch_route_nf(int nf, const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                                  int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
+    switch (nf) {
+        case 8:
+            if constexpr (NW <= 8)
+                return launch_route_inst<uint16_t, TF, NW, 8>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+            [[fallthrough]];
+        case 4: return launch_route_inst<uint16_t, TF, NW, 4>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+        case 2: return launch_route_inst<uint16_t, TF, NW, 2>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+        default: return launch_route_inst<uint16_t, TF, NW, 1>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    }
 }
 
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
-    const int T = s.T, d = s.d_model, E = s.E;
-    const int tok = route_chunk_tokens(s);
-    const unsigned grid = static_cast<unsigned>((T + tok - 1) / tok);
-    const size_t lds = static_cast<size_t>(tok) * (E + 1) * 4 + static_cast<size_t>(E) * 4;
-    if (lds > 48 * 1024) {      // more LDS than the default per-block limit: raise it for these kernels
-        hipError_t ea = hipSuccess;
-        if (s.dtype == MOE_BF16 && tok == 64)
-            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<uint16_t, 4>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        else if (s.dtype == MOE_BF16)
-            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<uint16_t, 1>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        else
-            ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&route_fused_kernel<float, 1>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (ea != hipSuccess) return ea;
-    }
-    if (s.dtype == MOE_BF16) {
-        const uint16_t* xp = static_cast<const uint16_t*>(x);
-        const uint16_t* wp = static_cast<const uint16_t*>(w_gate);
-        if (tok == 64)
-            hipLaunchKernelGGL((route_fused_kernel<uint16_t, 4>), dim3(grid), dim3(256), lds, st, xp, wp, bias, idx,
-                               gate, margin, chunk_hist, T, d, E, s.k, s.renormalize);
-        else
-            hipLaunchKernelGGL((route_fused_kernel<uint16_t, 1>), dim3(grid), dim3(256), lds, st, xp, wp, bias, idx,
-                               gate, margin, chunk_hist, T, d, E, s.k, s.renormalize);
-    } else {
-        hipLaunchKernelGGL((route_fused_kernel<float, 1>), dim3(grid), dim3(256), lds, st,
-                           static_cast<const float*>(x), static_cast<const float*>(w_gate), bias, idx, gate, margin,
-                           chunk_hist, T, d, E, s.k, s.renormalize);
-    }
-    return hipGetLastError();
+    if (s.dtype != MOE_BF16)
+        return launch_route_inst<float, 1, 4, 1>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    const RouteCfg c = route_cfg(s);
+    if (c.nw == 16) return launch_route_nf<1, 16>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    if (c.tok == 32) return launch_route_nf<2, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    return launch_route_nf<1, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
 }
 
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
