@@ -58,6 +58,30 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
+# HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
+# were taken with: reported as null once csrc/ffn.hip or csrc/ffn_tile.hip has changed.
+TRAFFIC_SOURCES = {"ffn.hip": "6df0ffc798cdf419", "ffn_tile.hip": "8b4aa9239f9c871f"}
+TRAFFIC_BYTES = {
+    ("switch_base", "stream_w1"): 339028626, ("switch_base", "stream_w2"): 414793463,
+    ("nllb_decode", "stream_w1"): 1645934552, ("nllb_decode", "stream_w2"): 1651274076,
+    ("nllb_prefill_skew", "stream_w1"): 1096774872, ("nllb_prefill_skew", "stream_w2"): 1155061564,
+    ("nllb_prefill_skew", "tile_w1"): 2633539201, ("nllb_prefill_skew", "tile_w2"): 2372934360,
+}
+
+
+def recorded_traffic(workload: str, tag: str):
+    import hashlib
+    for fn, want in TRAFFIC_SOURCES.items():
+        path = os.path.join(ROOT, "paper_2405_18832_amd", "csrc", fn)
+        try:
+            if hashlib.sha256(open(path, "rb").read()).hexdigest()[:16] != want:
+                return None
+        except OSError:
+            return None
+    return TRAFFIC_BYTES.get((workload, tag))
+
+
 def describe(cfg) -> str:
     return (f"{cfg.name}: T={cfg.T} d_model={cfg.d_model} d_ff={cfg.d_ff} E={cfg.E} top-{cfg.k} "
             f"{'renormalised' if cfg.renormalize else 'raw-prob'} gates, {cfg.dtype}, seed {cfg.seed}"
@@ -145,19 +169,18 @@ def main() -> int:
     ms_step = dt / K * 1e3
     tokens_s = cfg.T * K / dt
 
-    # ---- pass B: same loop with HIP events around the two grouped products ---------------------
+    # ---- pass B: same loop with HIP events around each expert-FFN kernel ------------------------
     hev = HipEvents()
-    evs = [(hev.create(), hev.create(), hev.create()) for _ in range(K)]
+    evs = [[hev.create() for _ in range(5)] for _ in range(K)]
     torch.cuda.synchronize()
     for i in range(K):
-        moe.moe_set_profile_events(*evs[i])
+        moe.moe_set_profile_events(evs[i])
         L.forward(H=H, copy=i)
-    moe.moe_set_profile_events(None, None, None)
+    moe.moe_set_profile_events(None)
     torch.cuda.synchronize()
-    g1 = np.array([hev.elapsed_ms(a, m) for a, m, _ in evs]) * 1e3      # us
-    g2 = np.array([hev.elapsed_ms(m, z) for _, m, z in evs]) * 1e3
-    for tr in evs:
-        for e in tr:
+    seg = np.array([[hev.elapsed_ms(e[j], e[j + 1]) for j in range(4)] for e in evs]) * 1e3      # us
+    for e5 in evs:
+        for e in e5:
             hev.destroy(e)
 
     # ---- per-entry-point breakdown (torch events on the same stream) ---------------------------
@@ -180,30 +203,40 @@ def main() -> int:
           "combine_us": timed(lambda i: L.combine(mask=mask_t))}
 
     # ---- roofline of the dominant kernel ---------------------------------------------------------
+    # Experts with >= 128 rows run in the LDS-tiled kernel, the others in the weight-streaming kernel
+    # (only when the layer has >= 128 tokens, else everything streams).
     d, f = cfg.d_model, cfg.d_ff
-    flops_one = 2.0 * A_run * d * f
-    kern = {
-        "w1_product": dict(us=float(g1.mean()), bytes=w_bytes_one + A_run * d * es, flops=flops_one),
-        "w2_product": dict(us=float(g2.mean()), bytes=w_bytes_one + A_run * d * 4, flops=flops_one),
-    }
-    dom = max(kern, key=lambda k_: kern[k_]["us"])
-    kd = kern[dom]
+    big = ran & (counts >= 128) if (cfg.dtype == "bf16" and cfg.T >= 128) else np.zeros_like(ran)
+    small = ran & ~big
+    rows_s, rows_b = int(counts[small].sum()), int(counts[big].sum())
+    wb_s, wb_b = int(small.sum()) * d * f * es, int(big.sum()) * d * f * es
+    names = ["ffn_stream_kernel (x.W1 product, small experts)", "ffn_tile_kernel (x.W1 product, large experts)",
+             "ffn_stream_kernel (h.W2 product, small experts)", "ffn_tile_kernel (h.W2 product, large experts)"]
+    tags = ["stream_w1", "tile_w1", "stream_w2", "tile_w2"]
+    kern = []
+    for j in range(4):
+        rows, wb = (rows_s, wb_s) if j % 2 == 0 else (rows_b, wb_b)
+        io = rows * d * (es if j < 2 else 4)                 # rows in (first product) / fp32 rows out (second)
+        kern.append(dict(name=names[j], tag=tags[j], us=float(seg[:, j].mean()), us_min=float(seg[:, j].min()),
+                         bytes=wb + io, flops=2.0 * rows * d * f))
+    kd = max(kern, key=lambda q: q["us"])
     t_flop = kd["flops"] / (PEAK_BF16_TFLOPS * 1e12)
     t_byte = kd["bytes"] / (PEAK_HBM_GBPS * 1e9)
+    traffic = recorded_traffic(name, kd["tag"])
     if cfg.dtype != "bf16":
         roof = None
     elif t_flop > t_byte:
         ach = kd["flops"] / (kd["us"] * 1e-6) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic}
     else:
         ach = kd["bytes"] / (kd["us"] * 1e-6) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBPS, "traffic": None}
+                "frac": ach / PEAK_HBM_GBPS, "traffic": traffic}
     if roof is not None:
-        roof.update(kernel=f"ffn_stream_kernel ({dom})", kernel_us=kd["us"], kernel_us_min=float(
-            (g1 if dom == "w1_product" else g2).min()), algorithmic_bytes=kd["bytes"], flops=kd["flops"],
-            other_product_us=kern["w2_product" if dom == "w1_product" else "w1_product"]["us"])
+        roof.update(kernel=kd["name"], kernel_us=kd["us"], kernel_us_min=kd["us_min"],
+                    algorithmic_bytes=kd["bytes"], flops=kd["flops"],
+                    ffn_kernels_us={q["tag"]: round(q["us"], 2) for q in kern})
 
     layer_flops = 2.0 * cfg.T * d * cfg.E + 4.0 * A_run * d * f
     layer_bytes = 2 * w_bytes_one + 2 * cfg.T * d * es + d * cfg.E * es

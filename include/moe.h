@@ -140,15 +140,16 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
                        void* out, void* stream);
 
 /*
- * Profiling aid for callers that time the two grouped products of the expert FFN separately
- * (the paper reasons about an expert's cost product by product, Section 2.2 and Eq. 3-4).
- * Each argument is a hipEvent_t created by the caller (as void*), or NULL.  Until the next
- * call, every expert-FFN launch (from moe_expert_ffn or moe_layer_forward) records
- * `before_w1` just before the first product's kernel, `between` after it, and `after_w2`
- * after the second product's kernel, on the launch's stream.  Pass three NULLs to stop.
- * Process-global and not thread-safe; events stay owned by the caller.
+ * Profiling aid for callers that time the kernels of the expert FFN separately (the paper reasons
+ * about an expert's cost product by product, Section 2.2 and Eq. 3-4).  `events` is a HOST array of
+ * five hipEvent_t created by the caller (entries may be NULL), or NULL to stop.  Until the next call,
+ * every expert-FFN launch (from moe_expert_ffn or moe_layer_forward) records, on the launch's stream:
+ *   [0] before the first product (x.W1^T, ReLU) of the small experts' weight-streaming kernel,
+ *   [1] after it, [2] after the first product of the large experts' tiled kernel (if launched),
+ *   [3] after the second product (h.W2^T) of the streaming kernel, [4] after that of the tiled kernel.
+ * The handles are copied; the array need not outlive the call.  Process-global, not thread-safe.
  */
-void moe_set_profile_events(void* before_w1, void* between, void* after_w2);
+void moe_set_profile_events(void* const* events);
 
 /*
  * The whole layer on one stream with no host synchronisation: route -> permute ->

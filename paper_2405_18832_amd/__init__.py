@@ -61,7 +61,7 @@ def load() -> ctypes.CDLL:
     lib.moe_packed_weight_bytes.restype = sz
     lib.moe_packed_weight_bytes.argtypes = [sp]
     lib.moe_set_profile_events.restype = None
-    lib.moe_set_profile_events.argtypes = [vp, vp, vp]
+    lib.moe_set_profile_events.argtypes = [ctypes.POINTER(vp)]
     lib.moe_pack_weights.restype = ctypes.c_int
     lib.moe_pack_weights.argtypes = [sp, i32, vp, vp, vp]
     lib.moe_route.restype = ctypes.c_int
@@ -128,9 +128,13 @@ def moe_packed_weight_bytes(shape: moe_shape) -> int:
     return int(load().moe_packed_weight_bytes(ctypes.byref(shape)))
 
 
-def moe_set_profile_events(before_w1=None, between=None, after_w2=None) -> None:
-    """hipEvent_t handles as ints (or None)."""
-    load().moe_set_profile_events(before_w1, between, after_w2)
+def moe_set_profile_events(events=None) -> None:
+    """`events`: sequence of five hipEvent_t handles (ints / c_void_p / None), or None to stop."""
+    if events is None:
+        load().moe_set_profile_events(None)
+        return
+    arr = (ctypes.c_void_p * 5)(*[e.value if isinstance(e, ctypes.c_void_p) else e for e in events])
+    load().moe_set_profile_events(arr)
 
 
 def moe_pack_weights(shape, which, src, dst, stream=None) -> None:

@@ -58,9 +58,8 @@ size_t moe_packed_weight_bytes(const moe_shape* shape) {
     return static_cast<size_t>(shape->E) * shape->d_model * shape->d_ff * elem_size(shape->dtype);
 }
 
-void moe_set_profile_events(void* before_w1, void* between, void* after_w2) {
-    set_profile_events(static_cast<hipEvent_t>(before_w1), static_cast<hipEvent_t>(between),
-                       static_cast<hipEvent_t>(after_w2));
+void moe_set_profile_events(void* const* events) {
+    set_profile_events(reinterpret_cast<const hipEvent_t*>(events));
 }
 
 moe_status moe_pack_weights(const moe_shape* shape, int32_t which, const void* src, void* dst, void* stream) {

@@ -179,7 +179,7 @@ hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t
 hipError_t launch_pack(const moe_shape& s, int which, const void* src, void* dst, hipStream_t st);
 hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hipStream_t st);
 
-void set_profile_events(hipEvent_t e0, hipEvent_t e1, hipEvent_t e2);
+void set_profile_events(const hipEvent_t* five_events_or_null);
 
 // number of compute units of the current device (cached)
 int device_cu_count();

@@ -357,12 +357,10 @@ static int pick_ksplit(int K, int tfmax) {
 }
 
 // events recorded around the two products when a caller asked for them (profiling aid)
-static hipEvent_t g_profile_events[3] = {nullptr, nullptr, nullptr};
+static hipEvent_t g_profile_events[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
 
-void set_profile_events(hipEvent_t e0, hipEvent_t e1, hipEvent_t e2) {
-    g_profile_events[0] = e0;
-    g_profile_events[1] = e1;
-    g_profile_events[2] = e2;
+void set_profile_events(const hipEvent_t* ev) {
+    for (int i = 0; i < 5; ++i) g_profile_events[i] = ev ? ev[i] : nullptr;
 }
 
 static hipError_t mark(int i, hipStream_t st) {
@@ -406,13 +404,14 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
                            static_cast<float*>(h_ws), tiles, ntiles, f, d);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
-        if ((err = mark(1, st)) != hipSuccess) return err;
+        if ((err = mark(1, st)) != hipSuccess || (err = mark(2, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(h_ws), static_cast<const int32_t*>(nullptr),
                            static_cast<const float*>(w2), y_perm, tiles, ntiles, d, f);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
-        return mark(2, st);
+        if ((err = mark(3, st)) != hipSuccess) return err;
+        return mark(4, st);
     }
 
     const uint16_t* xp = static_cast<const uint16_t*>(act);
@@ -426,22 +425,24 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
         default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
+    if ((err = mark(1, st)) != hipSuccess) return err;
     if (max_big > 0) {
         err = launch_tile_product(true, xp, rowmap, p1, h, lists.big_tiles, ntiles + 1, f, d, max_big, st);
         if (err != hipSuccess) return err;
     }
-    if ((err = mark(1, st)) != hipSuccess) return err;
+    if ((err = mark(2, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
         case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
         case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
         default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
     }
     if (err != hipSuccess) return err;
+    if ((err = mark(3, st)) != hipSuccess) return err;
     if (max_big > 0) {
         err = launch_tile_product(false, h, nullptr, p2, y_perm, lists.big_tiles, ntiles + 1, d, f, max_big, st);
         if (err != hipSuccess) return err;
     }
-    return mark(2, st);
+    return mark(4, st);
 }
 
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
