@@ -252,7 +252,14 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         if (rounds > 0) stride = (nbu + rounds - 1) / rounds;
         if (static_cast<int>(blockIdx.x) >= stride) return;
     }
-    for (int bu = blockIdx.x; bu < nbu; bu += stride) {
+    // Blocks go to the 8 XCDs round-robin and each XCD has its own L2: give the blocks of one XCD
+    // consecutive units, i.e. the column groups of the same tile, so that the tile's activation rows are
+    // fetched into that L2 once instead of into all eight.
+    const int pb = (stride % 8 == 0) ? static_cast<int>(blockIdx.x & 7) * (stride >> 3) + static_cast<int>(blockIdx.x >> 3)
+                                     : static_cast<int>(blockIdx.x);
+    for (int base = 0; base < nbu; base += stride) {
+        const int bu = base + pb;
+        if (bu >= nbu) break;                             // block-uniform
         const Tile tl = tiles[bu / ngchunks];
         const int ng = (bu % ngchunks) * NGB + ngs;
         const bool active = ng < ngroups;                 // wave-uniform
