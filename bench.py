@@ -210,12 +210,12 @@ def main() -> int:
     small = ran & ~big
     rows_s, rows_b = int(counts[small].sum()), int(counts[big].sum())
     wb_s, wb_b = int(small.sum()) * d * f * es, int(big.sum()) * d * f * es
-    names = ["ffn_stream_kernel (x.W1 product, small experts)", "ffn_tile_kernel (x.W1 product, large experts)",
-             "ffn_stream_kernel (h.W2 product, small experts)", "ffn_tile_kernel (h.W2 product, large experts)"]
-    tags = ["stream_w1", "tile_w1", "stream_w2", "tile_w2"]
+    names = ["ffn_tile_kernel (x.W1 product, large experts)", "ffn_stream_kernel (x.W1 product, small experts)",
+             "ffn_tile_kernel (h.W2 product, large experts)", "ffn_stream_kernel (h.W2 product, small experts)"]
+    tags = ["tile_w1", "stream_w1", "tile_w2", "stream_w2"]
     kern = []
     for j in range(4):
-        rows, wb = (rows_s, wb_s) if j % 2 == 0 else (rows_b, wb_b)
+        rows, wb = (rows_b, wb_b) if j % 2 == 0 else (rows_s, wb_s)
         io = rows * d * (es if j < 2 else 4)                 # rows in (first product) / fp32 rows out (second)
         kern.append(dict(name=names[j], tag=tags[j], us=float(seg[:, j].mean()), us_min=float(seg[:, j].min()),
                          bytes=wb + io, flops=2.0 * rows * d * f))

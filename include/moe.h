@@ -144,9 +144,9 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
  * about an expert's cost product by product, Section 2.2 and Eq. 3-4).  `events` is a HOST array of
  * five hipEvent_t created by the caller (entries may be NULL), or NULL to stop.  Until the next call,
  * every expert-FFN launch (from moe_expert_ffn or moe_layer_forward) records, on the launch's stream:
- *   [0] before the first product (x.W1^T, ReLU) of the small experts' weight-streaming kernel,
- *   [1] after it, [2] after the first product of the large experts' tiled kernel (if launched),
- *   [3] after the second product (h.W2^T) of the streaming kernel, [4] after that of the tiled kernel.
+ *   [0] before the first product (x.W1^T, ReLU) of the large experts' tiled kernel (if launched),
+ *   [1] after it, [2] after the first product of the small experts' weight-streaming kernel,
+ *   [3] after the second product (h.W2^T) of the tiled kernel, [4] after that of the streaming kernel.
  * The handles are copied; the array need not outlive the call.  Process-global, not thread-safe.
  */
 void moe_set_profile_events(void* const* events);

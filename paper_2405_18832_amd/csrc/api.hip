@@ -114,7 +114,7 @@ moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, offsets, mask, y_perm, at<void>(ws, L.h),
                                       at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big), at<int32_t>(ws, L.ntiles),
-                                      static_cast<hipStream_t>(stream)));
+                                      at<float>(ws, L.partials), static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_t* inv_perm,
@@ -154,7 +154,7 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     int32_t* hist = at<int32_t>(ws, L.hist);
     int32_t* tokmap = at<int32_t>(ws, L.tokmap);
     const TileLists lists = ffn_tile_lists(*shape, at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big),
-                                           at<int32_t>(ws, L.ntiles));
+                                           at<int32_t>(ws, L.ntiles), at<float>(ws, L.partials));
     hipError_t e;
     int nchunks = 0;
     const int tok = route_chunk_tokens(*shape);

@@ -51,11 +51,17 @@ struct Tile {
 // kBigTileRows rows); smaller experts are weight-streaming work.
 constexpr int kBigTileRows = 256;
 constexpr int kBigMinRows = 128;
+// The LDS-tiled kernel cuts the units of its last, partly filled round along K; the parts leave fp32
+// partial tiles (kBigTileRows x 256) in the workspace and are handed out through a counter.
+constexpr int kSplitSlots = 256;        // partial tiles in the workspace
+constexpr int kSplitCounter = 2;        // ints [2] and [3] of the `ntiles` array: the part counters of the
+                                        // first and of the second product
 
 struct TileLists {
     Tile* small_tiles;     // capacity A / small_rows + E
     Tile* big_tiles;       // capacity A / kBigTileRows + E (unused when big_min == 0)
-    int32_t* ntiles;       // [0] small count, [1] big count
+    int32_t* ntiles;       // [0] small count, [1] big count, [2], [3] part counters of the tiled products
+    float* partials;       // kSplitSlots partial tiles (nullptr when big_min == 0)
     int small_rows;        // rows per small tile
     int big_min;           // experts with >= big_min rows are "big"; 0 = none
 };
@@ -89,6 +95,7 @@ __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLis
             out[base + i] = t;
         }
         if (e == MOE_MAX_E - 1) tl.ntiles[pass] = scan[e];
+        if (pass == 0 && e < 2) tl.ntiles[kSplitCounter + e] = 0;
         if (tl.big_min <= 0 && pass == 0) {      // no large experts possible
             if (e == 0) tl.ntiles[1] = 0;
             break;
@@ -100,7 +107,7 @@ __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLis
 // ---- workspace ----------------------------------------------------------------
 struct WsLayout {
     size_t hist;       // int32 [ceil(T/16), E]  chunk histograms / slot bases of the counting sort
-    size_t ntiles;     // int32 [64]  ([0] = tiles of small experts, [1] = tiles of large experts)
+    size_t ntiles;     // int32 [64]  ([0] = tiles of small experts, [1] = of large experts, [2], [3] counters)
     size_t tiles;      // Tile [A/16 + E + 1]   row tiles of the weight-streaming kernel
     size_t tiles_big;  // Tile [A/256 + E + 1]  row tiles of the LDS-tiled kernel
     size_t h;          // dtype [A, f]
@@ -113,6 +120,7 @@ struct WsLayout {
     size_t mask;       // uint8 [E]
     size_t tokmap;     // int32 [A]  token row of each permuted position
     size_t y_perm;     // float [A, d]
+    size_t partials;   // float [kSplitSlots, 256, 256]  (only when an expert can reach kBigMinRows rows)
     size_t total;
 };
 
@@ -143,6 +151,8 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.mask = take(E);
     L.tokmap = take(A * 4);
     L.y_perm = take(A * s.d_model * 4);
+    const bool big = s.dtype == MOE_BF16 && s.T >= kBigMinRows;
+    L.partials = take(big ? static_cast<size_t>(kSplitSlots) * kBigTileRows * 256 * 4 : 0);
     L.total = off;
     return L;
 }
@@ -157,7 +167,7 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
                                 uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st);
-TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws);
+TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws, float* partials_ws);
 hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
 int ffn_tile_rows(const moe_shape& s);
@@ -165,14 +175,16 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
                                   const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
                                   hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
-                               void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
-                               hipStream_t st);
+                               void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
+                               float* partials, int N, int K, hipStream_t st);
+int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
                           int32_t* hist_ws, hipStream_t st);
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm,
-                             void* h_ws, Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, hipStream_t st);
+                             void* h_ws, Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
+                             hipStream_t st);
 hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t* inv_perm,
                           const int32_t* idx, const float* gate, const uint8_t* mask, void* out,
                           hipStream_t st);

@@ -6,7 +6,7 @@
 // (Section 2.2), is what shapes the kernel below: it streams every active expert's weights
 // exactly once at full memory bandwidth while the few token rows ride along as the other MFMA
 // operand.
-#include "common.hpp"
+#include "tile_schedule.hpp"
 
 namespace moe {
 
@@ -232,7 +232,12 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          void* __restrict__ outp,
                                                          const Tile* __restrict__ tiles,
                                                          const int32_t* __restrict__ ntiles_p, int N,
-                                                         int K, int balance) {
+                                                         int K, int balance,
+                                                         const Tile* __restrict__ big_tiles,
+                                                         const float* __restrict__ partials, int tile_grid) {
+    // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
+    // overlap with the rows of the small experts below)
+    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -321,7 +326,7 @@ int device_cu_count() {
 template <int TFMAX, int KSPLIT, bool FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
-                                hipStream_t st) {
+                                const Tile* big_tiles, const float* partials, hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -330,26 +335,27 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
         per_cu = n;
     }
     long grid = static_cast<long>(device_cu_count()) * per_cu;
-    if (grid > max_units) grid = max_units;
+    if (grid > max_units && partials == nullptr) grid = max_units;   // with partial tiles to add: all blocks
     if (grid < 1) grid = 1;
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K, TFMAX <= 2 ? 1 : 0);
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid());
     return hipGetLastError();
 }
 
 template <int TFMAX, bool FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
-                                  long max_tiles, hipStream_t st) {
+                                  long max_tiles, const Tile* big_tiles, const float* partials, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
-        return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups, st);
+        return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
+                                              big_tiles, partials, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                                  max_tiles * ((ngroups + 1) / 2), st);
+                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, st);
     return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 3) / 4), st);
+                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -379,7 +385,7 @@ static int ffn_tfmax(const moe_shape& s) { return s.T <= 16 ? 1 : (s.T <= 32 ? 2
 
 int ffn_tile_rows(const moe_shape& s) { return s.dtype == MOE_BF16 ? 16 * ffn_tfmax(s) : 16; }
 
-TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws) {
+TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws, float* partials_ws) {
     TileLists l;
     l.small_tiles = small_ws;
     l.big_tiles = big_ws;
@@ -387,6 +393,7 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
     l.small_rows = ffn_tile_rows(s);
     // a large expert needs kBigMinRows rows, and an expert holds at most T rows
     l.big_min = (s.dtype == MOE_BF16 && s.T >= kBigMinRows) ? kBigMinRows : 0;
+    l.partials = l.big_min > 0 ? partials_ws : nullptr;
     return l;
 }
 
@@ -399,25 +406,27 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     const Tile* tiles = lists.small_tiles;
     const int32_t* ntiles = lists.ntiles;
     const long max_tiles = A / tile_rows + (E < A ? E : A);
-    const long max_big = lists.big_min > 0 ? A / kBigTileRows + (E < A / lists.big_min ? E : A / lists.big_min) : 0;
+    const bool big = lists.big_min > 0;
+    int32_t* part1 = lists.ntiles + kSplitCounter;
+    int32_t* part2 = part1 + 1;
     hipError_t err;
     if ((err = mark(0, st)) != hipSuccess) return err;
 
     if (s.dtype == MOE_F32) {
         const long g1 = max_tiles * ((f + 255) / 256), g2 = max_tiles * ((d + 255) / 256);
         const long cap = static_cast<long>(device_cu_count()) * 8;
+        if ((err = mark(1, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(static_cast<unsigned>(g1 < cap ? g1 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(act), rowmap, static_cast<const float*>(w1),
                            static_cast<float*>(h_ws), tiles, ntiles, f, d);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
-        if ((err = mark(1, st)) != hipSuccess || (err = mark(2, st)) != hipSuccess) return err;
+        if ((err = mark(2, st)) != hipSuccess || (err = mark(3, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(h_ws), static_cast<const int32_t*>(nullptr),
                            static_cast<const float*>(w2), y_perm, tiles, ntiles, d, f);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
-        if ((err = mark(3, st)) != hipSuccess) return err;
         return mark(4, st);
     }
 
@@ -426,36 +435,41 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     const uint16_t* p2 = static_cast<const uint16_t*>(w2);
     uint16_t* h = static_cast<uint16_t*>(h_ws);
     const int ks1 = pick_ksplit(d, ffn_tfmax(s)), ks2 = pick_ksplit(f, ffn_tfmax(s));
-    switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
-        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, st); break;
+    const Tile* bt = lists.big_tiles;
+    const float* pt = big ? lists.partials : nullptr;
+    // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
+    // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
+    if (big) {
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, st);
+        if (err != hipSuccess) return err;
     }
-    if (err != hipSuccess) return err;
     if ((err = mark(1, st)) != hipSuccess) return err;
-    if (max_big > 0) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, lists.big_tiles, ntiles + 1, f, d, max_big, st);
-        if (err != hipSuccess) return err;
-    }
-    if ((err = mark(2, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
-        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
-        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, st); break;
+        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
+        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
+        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
     }
     if (err != hipSuccess) return err;
-    if ((err = mark(3, st)) != hipSuccess) return err;
-    if (max_big > 0) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, lists.big_tiles, ntiles + 1, d, f, max_big, st);
+    if ((err = mark(2, st)) != hipSuccess) return err;
+    if (big) {
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, st);
         if (err != hipSuccess) return err;
     }
+    if ((err = mark(3, st)) != hipSuccess) return err;
+    switch (ffn_tfmax(s)) {
+        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
+        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
+        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
+    }
+    if (err != hipSuccess) return err;
     return mark(4, st);
 }
 
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
-                             Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, hipStream_t st) {
-    const TileLists lists = ffn_tile_lists(s, tiles_ws, tiles_big_ws, ntiles_ws);
+                             Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
+                             hipStream_t st) {
+    const TileLists lists = ffn_tile_lists(s, tiles_ws, tiles_big_ws, ntiles_ws, partials_ws);
     hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, s.E, s.T * s.k, lists);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;

@@ -14,12 +14,14 @@
 // 4 weight fragments (MFMA A operand) x 8 row fragments (B operand) of 16x16x32 per 32-k step,
 // 128 accumulator registers.  Blocks are persistent over (row tile, column tile) pairs taken
 // from the device-built list of large-expert row tiles.
-#include "common.hpp"
+#include <type_traits>
+
+#include "tile_schedule.hpp"
 
 namespace moe {
 
 constexpr int kTM = kBigTileRows;   // 256 rows
-constexpr int kTN = 256;            // columns
+constexpr int kTN = kTileCols;      // 256 columns
 constexpr int kTK = 32;             // k per LDS stage
 constexpr int kStages = 4;          // ring of LDS stages: one being consumed, up to three in flight
 constexpr int kOperandBytes = kTM * kTK * 2;        // 16 KiB per operand per stage
@@ -28,39 +30,42 @@ constexpr int kStageBytes = 2 * kOperandBytes;      // 32 KiB per stage
 typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
 
-// 16 bytes per lane from global memory straight into LDS at `lds_base + 16 * lane` (no registers)
-__device__ __forceinline__ void copy16_to_lds(const void* src, unsigned char* lds_base) {
-    __builtin_amdgcn_global_load_lds((gptr_t)(src), (lptr_t)(lds_base), 16, 0, 0);
+// 16 bytes per lane from global memory straight into LDS at `lds_base + 16 * lane` (no registers);
+// `lds_base` (an LDS byte address) is the same for the whole wavefront and goes into M0.  Written as inline assembly: after the
+// compiler's own builtin for this instruction it makes every later wait for an LDS read a wait for all
+// outstanding LDS reads (as long as a copy is in flight, which here is always), and the loop below
+// depends on waiting only for the oldest ones.  The copies are counted by vmcnt; the code waits for
+// them explicitly, and orders them against LDS reads with barriers.  M0 is not live across statements
+// in compiled code for this target (the compiler sets it right before each use of its own).
+__device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory");
 }
 
-// One 32-k LDS stage of the inner product for one wavefront: 4 weight fragments x 8 row fragments.
-// `wbase` / `xbase` point at this lane's 16 bytes of the wavefront's first weight / row fragment;
-// the next fragment lies 1 KiB further.  LDS reads run one pair of row fragments ahead of the MFMAs
-// that consume them.
-__device__ __forceinline__ void tile_stage(const unsigned char* __restrict__ wbase,
-                                           const unsigned char* __restrict__ xbase, f32x4 (&acc)[4][8]) {
-    bf16x8 w[4], x0, x1, y0, y1;
+// Register fragments of one wavefront: the 4 weight fragments of a stage, double-buffered over stages,
+// and the 8 row fragments as 4 pairs.
+struct StageFrags {
+    bf16x8 w[2][4];
+    bf16x8 x[4][2];
+};
+
+__device__ __forceinline__ void lds_read_w(bf16x8 (&w)[4], const unsigned char* base) {
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf) w[nf] = *reinterpret_cast<const bf16x8*>(wbase + nf * 1024);
-    x0 = *reinterpret_cast<const bf16x8*>(xbase);
-    x1 = *reinterpret_cast<const bf16x8*>(xbase + 1024);
+    for (int nf = 0; nf < 4; ++nf) w[nf] = *reinterpret_cast<const bf16x8*>(base + nf * 1024);
+}
+
+__device__ __forceinline__ void lds_read_x(bf16x8 (&x)[2], const unsigned char* base, int pair) {
+    x[0] = *reinterpret_cast<const bf16x8*>(base + (2 * pair) * 1024);
+    x[1] = *reinterpret_cast<const bf16x8*>(base + (2 * pair + 1) * 1024);
+}
+
+// 4 weight fragments x row-fragment pair P: 8 MFMAs
+template <int P>
+__device__ __forceinline__ void mfma_pair(const bf16x8 (&w)[4], const bf16x8 (&x)[2], f32x4 (&acc)[4][8]) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        if (p + 1 < 4) {                                   // reads for the next pair go out first
-            y0 = *reinterpret_cast<const bf16x8*>(xbase + (2 * p + 2) * 1024);
-            y1 = *reinterpret_cast<const bf16x8*>(xbase + (2 * p + 3) * 1024);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int nf = 0; nf < 4; ++nf) {
-            acc[nf][2 * p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x0, acc[nf][2 * p], 0, 0, 0);
-            acc[nf][2 * p + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x1, acc[nf][2 * p + 1], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (p + 1 < 4) {
-            x0 = y0;
-            x1 = y1;
-        }
+    for (int nf = 0; nf < 4; ++nf) {
+        acc[nf][2 * P] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x[0], acc[nf][2 * P], 0, 0, 0);
+        acc[nf][2 * P + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nf], x[1], acc[nf][2 * P + 1], 0, 0, 0);
     }
 }
 
@@ -69,11 +74,12 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ rowmap,
                                                        const uint16_t* __restrict__ wpk,
                                                        void* __restrict__ outp, const Tile* __restrict__ tiles,
-                                                       const int32_t* __restrict__ ntiles_p, int N, int K) {
+                                                       const int32_t* __restrict__ ntiles_p,
+                                                       int32_t* __restrict__ part_counter,
+                                                       float* __restrict__ partials, int N, int K) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int next_part;
     // stage st: 16 row fragments at smem + st * kStageBytes, 16 weight fragments behind them
-    auto As = [&](int st) { return smem + st * kStageBytes; };
-    auto Bs = [&](int st) { return smem + st * kStageBytes + kOperandBytes; };
 
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int wm = wave >> 2, wn = wave & 3;
@@ -81,33 +87,39 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
     const int nblk = N >> 4, kblk = K >> 5;
     const int ntn = (N + kTN - 1) / kTN;
     const int ntiles = ntiles_p[0];
+    // LDS byte address of the first of the two fragments that this wavefront copies in, stage 0
+    const uint32_t copy_base = static_cast<uint32_t>(reinterpret_cast<size_t>((lptr_t)smem)) + 2 * wave * 1024;
 
-    // Unit order.  Blocks are handed to the 8 XCDs round-robin, and each XCD has its own L2.  The blocks
-    // of one XCD therefore work, at any time, on a compact GM x GN patch of (row tile, column tile) space,
-    // so that its L2 serves every activation panel GN times and every weight panel GM times; the 8 XCDs
-    // take 8 patches of the same column group (same weight panels, served to the others by the
-    // last-level cache).  Falls back to row-major order when the grid does not split that way.
+    // Blocks are handed to the 8 XCDs round-robin, and each XCD has its own L2: block b takes position pb
+    // of a round, so that the blocks of one XCD hold G / 8 consecutive units, a GM x GN patch whose
+    // activation panels that L2 serves GN times and whose weight panels GM times.
     const int G = gridDim.x;
-    const int GN = min(ntn, 8);
-    const bool patches = (G % 8 == 0) && ((G / 8) % GN == 0);
-    const int S = patches ? G / 8 : 1;
-    const int GM = patches ? S / GN : 1;
-    const int nrg = (ntiles + GM - 1) / GM, ncg = (ntn + GN - 1) / GN;
-    const int ngroups = nrg * ncg;
-    const int total = patches ? ((ngroups + 7) / 8) * G : ntiles * ntn;
+    const TileSchedule sch = tile_schedule(ntiles, N, kblk, G, partials != nullptr);
+    const int pb = (G % 8 == 0) ? static_cast<int>(blockIdx.x & 7) * (G >> 3) + static_cast<int>(blockIdx.x >> 3)
+                                : static_cast<int>(blockIdx.x);
+    const int nleft = sch.R * sch.split;                // parts of the left-over units
 
-    for (int L = blockIdx.x; L < total; L += G) {
-        int mt, nt;
-        if (patches) {
-            const int grp = (L / G) * 8 + (blockIdx.x & 7), slot = blockIdx.x >> 3;
-            if (grp >= ngroups) continue;
-            mt = (grp % nrg) * GM + slot / GN;
-            nt = (grp / nrg) * GN + slot % GN;
-            if (mt >= ntiles || nt >= ntn) continue;
+    for (int it = 0;; ++it) {
+        int u, part = 0;
+        if (it < sch.rounds) {
+            u = it * G + pb;
         } else {
-            mt = L / ntn;
-            nt = L % ntn;
+            // left-over parts go to whichever block is free: a counter hands them out (which block
+            // computes a part has no influence on the result)
+            __syncthreads();
+            if (t == 0) next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
+            __syncthreads();
+            const int id = next_part;
+            if (id >= nleft) break;                     // block-uniform; every block gets here
+            u = sch.rounds * G + id / sch.split;
+            part = id % sch.split;
         }
+        const int nparts = (it < sch.rounds) ? 1 : sch.split;
+        int mt, nt;
+        unit_of(sch, u, mt, nt);
+        const int kb0 = kblk * part / nparts;                // kblk * kMaxSplit fits easily
+        const int kb1 = kblk * (part + 1) / nparts;
+        const int nk = kb1 - kb0;
         const Tile tl = tiles[mt];
         // This wavefront stages fragments 2*wave and 2*wave+1 of each operand.  A lane fetches the 16
         // bytes that belong at its own slot of the fragment: row (lane % 16), k-group (lane / 16).
@@ -117,9 +129,9 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         for (int i = 0; i < 2; ++i) {
             int row = tl.row0 + min((2 * wave + i) * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];
-            arow[i] = act + static_cast<size_t>(row) * K + g * 8;
+            arow[i] = act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8;
             const int nb = min(nt * 16 + 2 * wave + i, nblk - 1);
-            brow[i] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
+            brow[i] = wpk + ((static_cast<size_t>(tl.expert) * nblk + nb) * kblk + kb0) * 512 + lane * 8;
         }
 
         f32x4 acc[4][8];
@@ -128,33 +140,97 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        auto stage_in = [&](int st, int kb) {              // 4 copies per wavefront and stage
+        // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance
+        auto stage_in = [&](int st) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                copy16_to_lds(arow[i] + kb * 32, As(st) + (2 * wave + i) * 1024);
-                copy16_to_lds(brow[i] + static_cast<size_t>(kb) * 512, Bs(st) + (2 * wave + i) * 1024);
+                copy16_to_lds(arow[i], copy_base + st * kStageBytes + i * 1024);
+                copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
+                arow[i] += 32;
+                brow[i] += 512;
             }
         };
 
-        const int wave_w = (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
+        const int wave_w = kOperandBytes + (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
+        StageFrags fr;
+        // One stage of 32 k, software-pipelined across stages so that the MFMA pipe never waits for LDS.
+        // The iteration for stage j starts by making sure that stage j + 1 has landed for every wavefront
+        // (own copies by vmcnt, the others' by the barrier; __syncthreads() would drain every outstanding
+        // copy and empty the ring) and by refilling the slot of stage j - 1, which nobody reads any more,
+        // with stage j + 3.  The fragments of stage j are in registers by then, except row pair 3: every
+        // group of 8 MFMAs is followed by the LDS reads that refill the registers it has just freed with
+        // stage j + 1, so each read has at least 8 MFMAs to complete.  (At its first use of an LDS result
+        // after a global-to-LDS copy was issued the compiler waits for all outstanding LDS reads, not
+        // only the needed ones: here that is at the first MFMA, when only old reads are outstanding.)
+        // `steady`: at least three more stages follow, so nothing in the iteration is conditional.
+        auto iterate = [&](auto cbuf, auto steady, int j) {
+            constexpr int C = decltype(cbuf)::value;
+            constexpr bool STEADY = decltype(steady)::value;
+            const unsigned char* cur = smem + (j & (kStages - 1)) * kStageBytes;
+            const unsigned char* nxt = smem + ((j + 1) & (kStages - 1)) * kStageBytes;
+            const bool more = STEADY || j + 1 < nk;        // block-uniform
+            if (more) {
+                if (STEADY || j + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): stage j + 2 may be in flight
+                else __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0)
+                asm volatile("s_barrier" ::: "memory");
+                if (STEADY || j + 3 < nk) stage_in((j + 3) & (kStages - 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_pair<0>(fr.w[C], fr.x[0], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_read_x(fr.x[3], cur + wave_x, 3);
+            if (more) {
+                lds_read_w(fr.w[C ^ 1], nxt + wave_w);
+                lds_read_x(fr.x[0], nxt + wave_x, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_pair<1>(fr.w[C], fr.x[1], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) lds_read_x(fr.x[1], nxt + wave_x, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_pair<2>(fr.w[C], fr.x[2], acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) lds_read_x(fr.x[2], nxt + wave_x, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_pair<3>(fr.w[C], fr.x[3], acc);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
         __syncthreads();                 // every wavefront is done reading the previous unit's stages
 #pragma unroll
         for (int sidx = 0; sidx < kStages - 1; ++sidx)
-            if (sidx < kblk) stage_in(sidx, sidx);
-        for (int kb = 0; kb < kblk; ++kb) {
-            // stage kb must have landed; the copies of up to two later stages (4 each) may stay in flight
-            const int later = min(kStages - 2, kblk - 1 - kb);
-            if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
-            else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F74);     // vmcnt(4)
-            else __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
-            // ... for every wavefront, and nobody still reads stage kb-1.  A bare barrier: __syncthreads()
-            // would first drain every outstanding copy (its fence waits for vmcnt(0)) and empty the ring.
-            asm volatile("s_barrier" ::: "memory");
-            if (kb + kStages - 1 < kblk) stage_in((kb + kStages - 1) % kStages, kb + kStages - 1);
-            tile_stage(Bs(kb % kStages) + wave_w, As(kb % kStages) + wave_x, acc);
+            if (sidx < nk) stage_in(sidx);
+        if (nk > 2) __builtin_amdgcn_s_waitcnt(0x0F78);                  // stage 0 landed: vmcnt(8)
+        else if (nk > 1) __builtin_amdgcn_s_waitcnt(0x0F74);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        asm volatile("s_barrier" ::: "memory");
+        lds_read_w(fr.w[0], smem + wave_w);
+        lds_read_x(fr.x[0], smem + wave_x, 0);
+        lds_read_x(fr.x[1], smem + wave_x, 1);
+        lds_read_x(fr.x[2], smem + wave_x, 2);
+        int j = 0;
+        for (; j + 4 < nk; j += 2) {
+            iterate(std::integral_constant<int, 0>{}, std::true_type{}, j);
+            iterate(std::integral_constant<int, 1>{}, std::true_type{}, j + 1);
         }
+        // at most 4 stages are left, and j is even: the buffers keep alternating
+        if (j < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j);
+        if (j + 1 < nk) iterate(std::integral_constant<int, 1>{}, std::false_type{}, j + 1);
+        if (j + 2 < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j + 2);
+        if (j + 3 < nk) iterate(std::integral_constant<int, 1>{}, std::false_type{}, j + 3);
 
-        // epilogue: lane holds 4 consecutive columns of one row per accumulator
+        // Lane holds 4 consecutive columns of one row per accumulator.
+        if (nparts > 1) {
+            // part of a unit: the partial tile goes to the workspace; the next kernel adds the parts up
+            float* mine = partials + (static_cast<size_t>(u - sch.rounds * G) * nparts + part) * (kTM * kTN);
+#pragma unroll
+            for (int tf = 0; tf < 8; ++tf)
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+                    *reinterpret_cast<f32x4*>(mine + (wm * 128 + tf * 16 + r) * kTN + (wn * 4 + nf) * 16 + g * 4) =
+                        acc[nf][tf];
+            continue;
+        }
 #pragma unroll
         for (int tf = 0; tf < 8; ++tf) {
             const int lr = wm * 128 + tf * 16 + r;
@@ -164,16 +240,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = nt * 16 + wn * 4 + nf;
                 if (nb >= nblk) continue;
-                const int n = nb * 16 + g * 4;
-                const f32x4 v = acc[nf][tf];
-                if (FIRST) {
-                    uint2 pk;
-                    pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
-                    pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
-                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + rowoff + n) = pk;
-                } else {
-                    *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + rowoff + n) = v;
-                }
+                store_out<FIRST>(outp, rowoff + nb * 16 + g * 4, acc[nf][tf]);
             }
         }
     }
@@ -181,33 +248,32 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 
 template <bool FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
-                              const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
-                              hipStream_t st) {
+                              const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
+                              int K, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
     constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
-    static int per_cu = 0;
-    if (per_cu == 0) {
+    static bool configured = false;
+    if (!configured) {
         hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (ea != hipSuccess) return ea;
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 512, lds) != hipSuccess || n <= 0) n = 1;
-        per_cu = n;
+        configured = true;
     }
-    const long ntn = (N + kTN - 1) / kTN;
-    long grid = static_cast<long>(device_cu_count()) * per_cu;
-    if (grid > max_tiles * ntn) grid = max_tiles * ntn;
-    if (grid < 1) grid = 1;
+    // Always the whole chip, one block per CU (the LDS ring allows no more): how many units there are is
+    // only known on the device, and few units are cut along K over blocks that would otherwise idle.
+    const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K);
+                       ntiles, part_counter, partials, N, K);
     return hipGetLastError();
 }
 
+int tile_product_grid() { return device_cu_count(); }
+
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
-                               void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K, long max_tiles,
-                               hipStream_t st) {
-    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles, st)
-                 : launch_tile<false>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles, st);
+                               void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
+                               float* partials, int N, int K, hipStream_t st) {
+    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, st)
+                 : launch_tile<false>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, st);
 }
 
 }  // namespace moe

@@ -366,7 +366,7 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
 
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
                                 uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st) {
-    const TileLists none{nullptr, nullptr, nullptr, 16, 0};
+    const TileLists none{nullptr, nullptr, nullptr, nullptr, 16, 0};
     hipLaunchKernelGGL(scan_finalize_kernel, dim3(1), dim3(1024), 0, st, chunk_hist, nchunks, E, counts, offsets, H,
                        hot_mask, mask_in, lists ? *lists : none, lists ? 1 : 0);
     return hipGetLastError();

@@ -1,0 +1,99 @@
+// Schedule of the LDS-tiled product over the (row tile, column tile) units of the large experts, shared
+// by the kernel that runs it (ffn_tile.hip) and the kernel that finishes it (ffn.hip).
+//
+// All units cost the same.  G blocks run U / G full rounds of whole units in a fixed, XCD-aware order.
+// The R = U mod G units left over would keep R blocks busy for a whole round and the rest of the chip
+// idle, so each of them is cut along K into `split` parts; blocks take parts from a counter as they
+// become free, and every part leaves an fp32 partial tile in the workspace.  The partial tiles are added
+// up in part order -- whichever block computed them -- by the next kernel on the stream: the kernel
+// boundary makes them visible across the XCDs' L2s without any fence.
+#pragma once
+#include "common.hpp"
+
+namespace moe {
+
+constexpr int kTileCols = 256;      // columns per unit (rows: kBigTileRows)
+constexpr int kMaxSplit = 8;        // parts per left-over unit, at most ...
+constexpr int kMinSplitSteps = 32;  // ... and 32-k steps per part, at least
+
+struct TileSchedule {
+    int ntiles, ntn;    // row tiles, column tiles
+    int rounds, R;      // full rounds of G units; units left over
+    int split;          // parts per left-over unit (1: not cut, written directly)
+    int GM, GN;         // patch of consecutive units: GM row tiles x GN column tiles
+};
+
+#ifdef __HIPCC__
+__device__ __forceinline__ TileSchedule tile_schedule(int ntiles, int N, int kblk, int G, bool have_partials) {
+    TileSchedule s;
+    s.ntiles = ntiles;
+    s.ntn = (N + kTileCols - 1) / kTileCols;
+    const int U = ntiles * s.ntn;
+    s.rounds = U / G;
+    s.R = U - s.rounds * G;
+    s.split = 1;
+    if (s.R > 0 && have_partials) {
+        const int by_blocks = G / s.R, by_steps = kblk / kMinSplitSteps, by_slots = kSplitSlots / s.R;
+        s.split = min(min(by_blocks, kMaxSplit), min(by_steps, by_slots));
+        if (s.split < 2) s.split = 1;
+    }
+    s.GN = min(s.ntn, 8);
+    s.GM = (G % 8 == 0 && (G / 8) % s.GN == 0) ? (G / 8) / s.GN : 1;
+    return s;
+}
+
+// Unit u of the ntiles x ntn grid.  Units are numbered so that a run of consecutive units is a compact
+// patch: column tiles in groups of GN, and inside a group GM row tiles at a time.  Every u in
+// [0, ntiles * ntn) maps to exactly one (row tile, column tile).
+__device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, int& nt) {
+    const int per_group = s.ntiles * s.GN;
+    const int cg = u / per_group;                       // the last group may hold fewer than GN columns
+    const int wn = min(s.GN, s.ntn - cg * s.GN);
+    const int v = u - cg * per_group;                   // < ntiles * wn
+    const int chunk = v / (s.GM * wn), slot = v - chunk * (s.GM * wn);
+    mt = chunk * s.GM + slot / wn;                      // < ntiles, also in a last, shorter chunk
+    nt = cg * s.GN + slot % wn;
+}
+
+// 4 values of one output row (FIRST: relu and bf16)
+template <bool FIRST>
+__device__ __forceinline__ void store_out(void* outp, size_t off, const f32x4 v) {
+    if (FIRST) {
+        uint2 pk;
+        pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
+        pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + off) = pk;
+    } else {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + off) = v;
+    }
+}
+
+// Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
+// Called by every thread of every block of the following kernel; 4 columns of a row per thread and step.
+template <bool FIRST>
+__device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
+                                                   const float* __restrict__ partials, void* __restrict__ outp,
+                                                   int N, int kblk, int G) {
+    if (ntiles_big <= 0 || partials == nullptr) return;
+    const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
+    if (s.split < 2) return;
+    constexpr int kQuads = kBigTileRows * kTileCols / 4;
+    const long total = static_cast<long>(s.R) * kQuads;
+    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+         i += static_cast<long>(gridDim.x) * blockDim.x) {
+        const int ru = static_cast<int>(i / kQuads), q = static_cast<int>(i % kQuads);
+        int mt, nt;
+        unit_of(s, s.rounds * G + ru, mt, nt);
+        const Tile tl = big_tiles[mt];
+        const int lr = q / (kTileCols / 4), c = nt * kTileCols + (q % (kTileCols / 4)) * 4;
+        if (lr >= tl.rows || c >= N) continue;
+        const float* base = partials + (static_cast<size_t>(ru) * s.split * kQuads + q) * 4;
+        f32x4 sum = *reinterpret_cast<const f32x4*>(base);
+        for (int p = 1; p < s.split; ++p)
+            sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
+        store_out<FIRST>(outp, static_cast<size_t>(tl.row0 + lr) * N + c, sum);
+    }
+}
+#endif
+
+}  // namespace moe

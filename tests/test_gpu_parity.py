@@ -231,7 +231,16 @@ def test_expert_ffn(gpu_lib, name):
     y2 = L.y_perm.cpu().numpy().astype(np.float64)
     owner = np.repeat(np.arange(cfg.E), r["counts"])
     on = mask_np[owner] == 1
-    assert np.array_equal(y2[on], y[on]) and np.isnan(y2[~on]).all()
+    assert np.isnan(y2[~on]).all()
+    # The rows of the experts that do run may differ from the unmasked run in summation order only: which
+    # large-expert tiles fall into the last scheduling round, and are therefore summed in K-slices, depends
+    # on how many tiles there are.  That is fp32 reassociation (1e-7 relative), which now and then moves an
+    # element of h across a bf16 rounding boundary: one ulp of h (2^-8) times one of the d_ff terms of y.
+    rms = np.sqrt(np.mean(y[on] ** 2)) if on.any() else 0.0
+    diff = np.abs(y2[on] - y[on])
+    say(f"[mask] {name}: max |masked - unmasked| = {(diff.max() if diff.size else 0.0) / max(rms, 1e-30):.2e} rms, "
+        f"{np.count_nonzero(diff)} of {diff.size} elements differ")
+    assert np.all(diff <= 1e-3 * rms)
 
 
 # ------------------------------------------------------------------------------ combine
