@@ -57,6 +57,17 @@ constexpr int kSplitSlots = 256;        // partial tiles in the workspace
 constexpr int kSplitCounter = 2;        // ints [2] and [3] of the `ntiles` array: the part counters of the
                                         // first and of the second product
 
+// Layout of the bf16 intermediate h = relu(x . W1^T) in the workspace: k-step-major, [d_ff / 32][A][32]
+// (A = T * k rows).  The second product consumes h 32 k at a time: the 32 values of consecutive rows
+// are then 64 bytes apart, so a 16-row MFMA operand fragment is one contiguous KiB and a row tile of a
+// k-step a contiguous run of full cache lines (row-major, each row would contribute half a line).
+// Element (row, n) lives at:
+#ifdef __HIPCC__
+__device__ __forceinline__ size_t h_index(int row, int n, int rows_total) {
+    return (static_cast<size_t>(n >> 5) * rows_total + row) * 32 + (n & 31);
+}
+#endif
+
 struct TileLists {
     Tile* small_tiles;     // capacity A / small_rows + E
     Tile* big_tiles;       // capacity A / kBigTileRows + E (unused when big_min == 0)
@@ -176,7 +187,7 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
                                   hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, hipStream_t st);
+                               float* partials, int N, int K, int rows_total, hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,

@@ -113,7 +113,8 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const int32_t* __restrict__ rowmap,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
-                                            const int K, const int kb0, const int kb1, f32x4* red) {
+                                            const int K, const int kb0, const int kb1, f32x4* red,
+                                            const int rows_total) {
     constexpr int PF = StreamPF<TFC>::value;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -138,15 +139,17 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
         for (int tf = 0; tf < TFC; ++tf) {
             int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
-            ap[tf] = act + static_cast<size_t>(row) * K + g * 8;
+            // first product: rows of x, row-major; second: rows of h, k-step-major
+            ap[tf] = FIRST ? act + static_cast<size_t>(row) * K + g * 8 : act + h_index(row, g * 8, rows_total);
         }
+        const size_t kstride = FIRST ? 32 : static_cast<size_t>(rows_total) * 32;   // elements per k-step
         bf16x8 a[PF][4], b[PF][TFC];
         auto issue = [&](int slot, int kb) {
 #pragma unroll
             for (int nf = 0; nf < 4; ++nf)
                 a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
 #pragma unroll
-            for (int tf = 0; tf < TFC; ++tf) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * 32);
+            for (int tf = 0; tf < TFC; ++tf) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * kstride);
         };
         auto fma = [&](int slot) {
 #pragma unroll
@@ -204,21 +207,11 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
         for (int tf = 0; tf < TFC; ++tf) {
             const int lr = tf * 16 + r;
             if (lr >= tl.rows) continue;
-            const size_t rowoff = static_cast<size_t>(tl.row0 + lr) * N;
 #pragma unroll
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = ng * 4 + nf;
                 if (nb >= nblk) continue;
-                const int n = nb * 16 + g * 4;
-                const f32x4 v = acc[nf][tf];
-                if (FIRST) {
-                    uint2 pk;
-                    pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
-                    pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
-                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + rowoff + n) = pk;
-                } else {
-                    *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + rowoff + n) = v;
-                }
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
             }
         }
     }
@@ -234,10 +227,11 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ ntiles_p, int N,
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
-                                                         const float* __restrict__ partials, int tile_grid) {
+                                                         const float* __restrict__ partials, int tile_grid,
+                                                         int rows_total) {
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid);
+    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -270,13 +264,13 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         const bool active = ng < ngroups;                 // wave-uniform
         const int tfc = (tl.rows + 15) >> 4;              // token fragments in use: block-uniform
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red);
+            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
     }
 }
 
@@ -326,7 +320,7 @@ int device_cu_count() {
 template <int TFMAX, int KSPLIT, bool FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
-                                const Tile* big_tiles, const float* partials, hipStream_t st) {
+                                const Tile* big_tiles, const float* partials, int rows_total, hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -339,23 +333,24 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     if (grid < 1) grid = 1;
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid());
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total);
     return hipGetLastError();
 }
 
 template <int TFMAX, bool FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
-                                  long max_tiles, const Tile* big_tiles, const float* partials, hipStream_t st) {
+                                  long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
+                                  hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
         return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                              big_tiles, partials, st);
+                                              big_tiles, partials, rows_total, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, st);
+                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, st);
     return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, st);
+                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -440,26 +435,26 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
     // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
     if (big) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, st);
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
-        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
-        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, st); break;
+        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
+        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
+        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
     if (big) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, st);
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
-        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
-        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, st); break;
+        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
+        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
+        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);

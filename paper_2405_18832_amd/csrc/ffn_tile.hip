@@ -5,7 +5,8 @@
 //   out[row, n] = sum_k act[row, k] * W_e[n, k]          (FIRST: relu, rounded to bf16)
 //
 // Block = 8 wavefronts on a 256 (rows) x 256 (columns) output tile, K in steps of 32 through a
-// ring of four LDS stages (the copies of three stages are in flight while one is consumed).  Both operands sit in LDS in MFMA-fragment order (16 x 32 fragments of
+// ring of four LDS stages of 32 KiB: the copies of two stages are in flight while two are being
+// read (the current one, and the next one into registers ahead of its MFMAs).  Both operands sit in LDS in MFMA-fragment order (16 x 32 fragments of
 // 1 KiB, one 16-byte piece per lane), so every LDS read of the inner loop is a conflict-free
 // 1 KiB wavefront read.  Global memory is copied straight into LDS (16 bytes per lane, no
 // registers in between): the packed weights are already in fragment order in HBM, and for the
@@ -23,7 +24,9 @@ namespace moe {
 constexpr int kTM = kBigTileRows;   // 256 rows
 constexpr int kTN = kTileCols;      // 256 columns
 constexpr int kTK = 32;             // k per LDS stage
-constexpr int kStages = 4;          // ring of LDS stages: one being consumed, up to three in flight
+constexpr int kStages = 4;          // ring of LDS stages: two being read, two in flight (a fifth, which
+                                    // fits, bought nothing: the copies are not limited by ring depth)
+constexpr int kAhead = kStages - 1; // the iteration for stage j issues the copies of stage j + kAhead
 constexpr int kOperandBytes = kTM * kTK * 2;        // 16 KiB per operand per stage
 constexpr int kStageBytes = 2 * kOperandBytes;      // 32 KiB per stage
 
@@ -40,6 +43,14 @@ typedef void __attribute__((address_space(3))) * lptr_t;
 __device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory");
+}
+
+// Wait until at most `stages` stages' worth of this wavefront's copies (4 each) are still in flight.
+__device__ __forceinline__ void wait_copies(int stages) {
+    if (stages >= 3) __builtin_amdgcn_s_waitcnt(0x0F7C);         // vmcnt(12)
+    else if (stages == 2) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
+    else if (stages == 1) __builtin_amdgcn_s_waitcnt(0x0F74);    // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0)
 }
 
 // Register fragments of one wavefront: the 4 weight fragments of a stage, double-buffered over stages,
@@ -76,9 +87,11 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        void* __restrict__ outp, const Tile* __restrict__ tiles,
                                                        const int32_t* __restrict__ ntiles_p,
                                                        int32_t* __restrict__ part_counter,
-                                                       float* __restrict__ partials, int N, int K) {
+                                                       float* __restrict__ partials, int N, int K,
+                                                       int rows_total) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ int next_part;
+    // between units, when no stage is in use, the first word of the ring passes the next part's number on
+    int* next_part = reinterpret_cast<int*>(smem);
     // stage st: 16 row fragments at smem + st * kStageBytes, 16 weight fragments behind them
 
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
@@ -107,9 +120,9 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             // left-over parts go to whichever block is free: a counter hands them out (which block
             // computes a part has no influence on the result)
             __syncthreads();
-            if (t == 0) next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
+            if (t == 0) *next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
             __syncthreads();
-            const int id = next_part;
+            const int id = *next_part;
             if (id >= nleft) break;                     // block-uniform; every block gets here
             u = sch.rounds * G + id / sch.split;
             part = id % sch.split;
@@ -129,7 +142,9 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         for (int i = 0; i < 2; ++i) {
             int row = tl.row0 + min((2 * wave + i) * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];
-            arow[i] = act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8;
+            // first product: rows of x, row-major; second: rows of h, k-step-major
+            arow[i] = FIRST ? act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8
+                            : act + h_index(row, kb0 * 32 + g * 8, rows_total);
             const int nb = min(nt * 16 + 2 * wave + i, nblk - 1);
             brow[i] = wpk + ((static_cast<size_t>(tl.expert) * nblk + nb) * kblk + kb0) * 512 + lane * 8;
         }
@@ -141,12 +156,13 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             for (int tf = 0; tf < 8; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance
+        const size_t kstride = FIRST ? 32 : static_cast<size_t>(rows_total) * 32;   // elements per k-step
         auto stage_in = [&](int st) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 copy16_to_lds(arow[i], copy_base + st * kStageBytes + i * 1024);
                 copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
-                arow[i] += 32;
+                arow[i] += kstride;
                 brow[i] += 512;
             }
         };
@@ -157,23 +173,26 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         // The iteration for stage j starts by making sure that stage j + 1 has landed for every wavefront
         // (own copies by vmcnt, the others' by the barrier; __syncthreads() would drain every outstanding
         // copy and empty the ring) and by refilling the slot of stage j - 1, which nobody reads any more,
-        // with stage j + 3.  The fragments of stage j are in registers by then, except row pair 3: every
+        // with stage j + kAhead.  The fragments of stage j are in registers by then, except row pair 3: every
         // group of 8 MFMAs is followed by the LDS reads that refill the registers it has just freed with
         // stage j + 1, so each read has at least 8 MFMAs to complete.  (At its first use of an LDS result
         // after a global-to-LDS copy was issued the compiler waits for all outstanding LDS reads, not
         // only the needed ones: here that is at the first MFMA, when only old reads are outstanding.)
-        // `steady`: at least three more stages follow, so nothing in the iteration is conditional.
+        // `steady`: stage j + kAhead exists, so nothing in the iteration is conditional.
+        int slot = 0;                                      // ring slot of stage j
         auto iterate = [&](auto cbuf, auto steady, int j) {
             constexpr int C = decltype(cbuf)::value;
             constexpr bool STEADY = decltype(steady)::value;
-            const unsigned char* cur = smem + (j & (kStages - 1)) * kStageBytes;
-            const unsigned char* nxt = smem + ((j + 1) & (kStages - 1)) * kStageBytes;
+            const int slot_next = slot + 1 == kStages ? 0 : slot + 1;
+            const int slot_free = slot == 0 ? kStages - 1 : slot - 1;          // held stage j - 1
+            const unsigned char* cur = smem + slot * kStageBytes;
+            const unsigned char* nxt = smem + slot_next * kStageBytes;
             const bool more = STEADY || j + 1 < nk;        // block-uniform
             if (more) {
-                if (STEADY || j + 2 < nk) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4): stage j + 2 may be in flight
-                else __builtin_amdgcn_s_waitcnt(0x0F70);                        // vmcnt(0)
+                // stages j + 2 ... j + kAhead - 1 (as far as they exist) may stay in flight
+                wait_copies(STEADY ? kAhead - 2 : min(j + kAhead - 1, nk - 1) - (j + 1));
                 asm volatile("s_barrier" ::: "memory");
-                if (STEADY || j + 3 < nk) stage_in((j + 3) & (kStages - 1));
+                if (STEADY || j + kAhead < nk) stage_in(slot_free);
             }
             __builtin_amdgcn_sched_barrier(0);
             mfma_pair<0>(fr.w[C], fr.x[0], acc);
@@ -194,30 +213,30 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             __builtin_amdgcn_sched_barrier(0);
             mfma_pair<3>(fr.w[C], fr.x[3], acc);
             __builtin_amdgcn_sched_barrier(0);
+            slot = slot_next;
         };
 
         __syncthreads();                 // every wavefront is done reading the previous unit's stages
 #pragma unroll
-        for (int sidx = 0; sidx < kStages - 1; ++sidx)
+        for (int sidx = 0; sidx < kAhead; ++sidx)
             if (sidx < nk) stage_in(sidx);
-        if (nk > 2) __builtin_amdgcn_s_waitcnt(0x0F78);                  // stage 0 landed: vmcnt(8)
-        else if (nk > 1) __builtin_amdgcn_s_waitcnt(0x0F74);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-        asm volatile("s_barrier" ::: "memory");
+        wait_copies(min(kAhead, nk) - 1);                  // stage 0 has landed ...
+        asm volatile("s_barrier" ::: "memory");           // ... for every wavefront
         lds_read_w(fr.w[0], smem + wave_w);
         lds_read_x(fr.x[0], smem + wave_x, 0);
         lds_read_x(fr.x[1], smem + wave_x, 1);
         lds_read_x(fr.x[2], smem + wave_x, 2);
         int j = 0;
-        for (; j + 4 < nk; j += 2) {
+        for (; j + 1 + kAhead < nk; j += 2) {
             iterate(std::integral_constant<int, 0>{}, std::true_type{}, j);
             iterate(std::integral_constant<int, 1>{}, std::true_type{}, j + 1);
         }
-        // at most 4 stages are left, and j is even: the buffers keep alternating
+        // at most kAhead + 1 stages are left, and j is even: the buffers keep alternating
         if (j < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j);
         if (j + 1 < nk) iterate(std::integral_constant<int, 1>{}, std::false_type{}, j + 1);
         if (j + 2 < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j + 2);
         if (j + 3 < nk) iterate(std::integral_constant<int, 1>{}, std::false_type{}, j + 3);
+        if (j + 4 < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j + 4);
 
         // Lane holds 4 consecutive columns of one row per accumulator.
         if (nparts > 1) {
@@ -235,12 +254,11 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         for (int tf = 0; tf < 8; ++tf) {
             const int lr = wm * 128 + tf * 16 + r;
             if (lr >= tl.rows) continue;
-            const size_t rowoff = static_cast<size_t>(tl.row0 + lr) * N;
 #pragma unroll
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = nt * 16 + wn * 4 + nf;
                 if (nb >= nblk) continue;
-                store_out<FIRST>(outp, rowoff + nb * 16 + g * 4, acc[nf][tf]);
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
             }
         }
     }
@@ -249,7 +267,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 template <bool FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                               const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
-                              int K, hipStream_t st) {
+                              int K, int rows_total, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
     constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
     static bool configured = false;
@@ -263,7 +281,7 @@ static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const 
     // only known on the device, and few units are cut along K over blocks that would otherwise idle.
     const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, part_counter, partials, N, K);
+                       ntiles, part_counter, partials, N, K, rows_total);
     return hipGetLastError();
 }
 
@@ -271,9 +289,10 @@ int tile_product_grid() { return device_cu_count(); }
 
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, hipStream_t st) {
-    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, st)
-                 : launch_tile<false>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, st);
+                               float* partials, int N, int K, int rows_total, hipStream_t st) {
+    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total, st)
+                 : launch_tile<false>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
+                                      st);
 }
 
 }  // namespace moe
