@@ -173,7 +173,18 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     if (shape->T == 0) return MOE_OK;
     e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
-    e = launch_expert_products(*shape, x, tokmap, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists, hs);
+    if (layer_gathers_kmajor(*shape)) {
+        // layers large enough for the tiled kernel: one pass gathers the token rows into the k-step-major
+        // layout that lets both kernels fetch operand rows as full cache lines
+        void* xk = at<void>(ws, L.x_kmajor);
+        e = launch_gather_kmajor(*shape, x, tokmap, xk, hs);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+        e = launch_expert_products(*shape, xk, nullptr, true, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
+                                   hs);
+    } else {
+        e = launch_expert_products(*shape, x, tokmap, false, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
+                                   hs);
+    }
     if (e != hipSuccess) return MOE_ERR_HIP;
     e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
     return from_hip(e);

@@ -132,6 +132,7 @@ struct WsLayout {
     size_t tokmap;     // int32 [A]  token row of each permuted position
     size_t y_perm;     // float [A, d]
     size_t partials;   // float [kSplitSlots, 256, 256]  (only when an expert can reach kBigMinRows rows)
+    size_t x_kmajor;   // bf16 [d/32, A, 32]  gathered token rows, k-step-major (same condition)
     size_t total;
 };
 
@@ -164,6 +165,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.y_perm = take(A * s.d_model * 4);
     const bool big = s.dtype == MOE_BF16 && s.T >= kBigMinRows;
     L.partials = take(big ? static_cast<size_t>(kSplitSlots) * kBigTileRows * 256 * 4 : 0);
+    L.x_kmajor = take(big ? A * s.d_model * es : 0);
     L.total = off;
     return L;
 }
@@ -182,12 +184,14 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
 hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
 int ffn_tile_rows(const moe_shape& s);
-hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
-                                  const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
+hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
+                                  const void* w1, const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
                                   hipStream_t st);
+bool layer_gathers_kmajor(const moe_shape& s);
+hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, int rows_total, hipStream_t st);
+                               float* partials, int N, int K, int rows_total, bool act_kmajor, hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,

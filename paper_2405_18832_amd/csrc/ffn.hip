@@ -114,7 +114,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
                                             const int K, const int kb0, const int kb1, f32x4* red,
-                                            const int rows_total) {
+                                            const int rows_total, const bool act_kmajor) {
     constexpr int PF = StreamPF<TFC>::value;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -139,10 +139,10 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
         for (int tf = 0; tf < TFC; ++tf) {
             int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
-            // first product: rows of x, row-major; second: rows of h, k-step-major
-            ap[tf] = FIRST ? act + static_cast<size_t>(row) * K + g * 8 : act + h_index(row, g * 8, rows_total);
+            // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
+            ap[tf] = act_kmajor ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
         }
-        const size_t kstride = FIRST ? 32 : static_cast<size_t>(rows_total) * 32;   // elements per k-step
+        const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
         bf16x8 a[PF][4], b[PF][TFC];
         auto issue = [&](int slot, int kb) {
 #pragma unroll
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
-                                                         int rows_total) {
+                                                         int rows_total, int act_kmajor) {
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
     if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total);
@@ -264,13 +264,13 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         const bool active = ng < ngroups;                 // wave-uniform
         const int tfc = (tl.rows + 15) >> 4;              // token fragments in use: block-uniform
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
+            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
+            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
+            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total);
+            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
     }
 }
 
@@ -320,7 +320,8 @@ int device_cu_count() {
 template <int TFMAX, int KSPLIT, bool FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
-                                const Tile* big_tiles, const float* partials, int rows_total, hipStream_t st) {
+                                const Tile* big_tiles, const float* partials, int rows_total, bool act_kmajor,
+                                hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -333,7 +334,7 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     if (grid < 1) grid = 1;
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total);
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total, act_kmajor ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -341,16 +342,16 @@ template <int TFMAX, bool FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
-                                  hipStream_t st) {
+                                  bool act_kmajor, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
         return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                              big_tiles, partials, rows_total, st);
+                                              big_tiles, partials, rows_total, act_kmajor, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, st);
+                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, st);
     return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, st);
+                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -393,8 +394,15 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
 }
 
 // the two grouped products over existing tile lists
-hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, const void* w1,
-                                  const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
+// The extra pass over the token rows pays once the layer is large (measured: a gain from 4 M elements of
+// gathered rows on, a small loss at 1.5 M, where the launch costs more than the better-shaped loads save).
+bool layer_gathers_kmajor(const moe_shape& s) {
+    return s.dtype == MOE_BF16 && s.T >= kBigMinRows &&
+           static_cast<long>(s.T) * s.k * s.d_model >= (4L << 20);
+}
+
+hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
+                                  const void* w1, const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
                                   hipStream_t st) {
     const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
     const int tile_rows = lists.small_rows;
@@ -435,26 +443,26 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
     // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
     if (big) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, st);
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
-        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
-        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, st); break;
+        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
     if (big) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, st);
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
-        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
-        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, st); break;
+        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
+        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
+        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);
@@ -468,7 +476,7 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
     hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, s.E, s.T * s.k, lists);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    return launch_expert_products(s, x_perm, nullptr, w1, w2, y_perm, h_ws, lists, st);
+    return launch_expert_products(s, x_perm, nullptr, false, w1, w2, y_perm, h_ws, lists, st);
 }
 
 }  // namespace moe

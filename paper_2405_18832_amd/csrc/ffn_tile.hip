@@ -88,7 +88,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ ntiles_p,
                                                        int32_t* __restrict__ part_counter,
                                                        float* __restrict__ partials, int N, int K,
-                                                       int rows_total) {
+                                                       int rows_total, int act_kmajor) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // between units, when no stage is in use, the first word of the ring passes the next part's number on
     int* next_part = reinterpret_cast<int*>(smem);
@@ -142,9 +142,9 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         for (int i = 0; i < 2; ++i) {
             int row = tl.row0 + min((2 * wave + i) * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];
-            // first product: rows of x, row-major; second: rows of h, k-step-major
-            arow[i] = FIRST ? act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8
-                            : act + h_index(row, kb0 * 32 + g * 8, rows_total);
+            // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
+            arow[i] = act_kmajor ? act + h_index(row, kb0 * 32 + g * 8, rows_total)
+                                 : act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8;
             const int nb = min(nt * 16 + 2 * wave + i, nblk - 1);
             brow[i] = wpk + ((static_cast<size_t>(tl.expert) * nblk + nb) * kblk + kb0) * 512 + lane * 8;
         }
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             for (int tf = 0; tf < 8; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance
-        const size_t kstride = FIRST ? 32 : static_cast<size_t>(rows_total) * 32;   // elements per k-step
+        const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
         auto stage_in = [&](int st) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 template <bool FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                               const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
-                              int K, int rows_total, hipStream_t st) {
+                              int K, int rows_total, bool act_kmajor, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
     constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
     static bool configured = false;
@@ -281,7 +281,7 @@ static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const 
     // only known on the device, and few units are cut along K over blocks that would otherwise idle.
     const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, part_counter, partials, N, K, rows_total);
+                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -289,10 +289,11 @@ int tile_product_grid() { return device_cu_count(); }
 
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, int rows_total, hipStream_t st) {
-    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total, st)
+                               float* partials, int N, int K, int rows_total, bool act_kmajor, hipStream_t st) {
+    return first ? launch_tile<true>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
+                                     act_kmajor, st)
                  : launch_tile<false>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                                      st);
+                                      act_kmajor, st);
 }
 
 }  // namespace moe
