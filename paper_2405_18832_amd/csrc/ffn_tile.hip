@@ -157,14 +157,19 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 
         // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance
         const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
-        auto stage_in = [&](int st) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
+        auto copy_piece = [&](int st, int q) {             // q = 0 ... 3: row fragment 0, weight 0, row 1, weight 1
+            const int i = q >> 1;
+            if ((q & 1) == 0) {
                 copy16_to_lds(arow[i], copy_base + st * kStageBytes + i * 1024);
-                copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
                 arow[i] += kstride;
+            } else {
+                copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
                 brow[i] += 512;
             }
+        };
+        auto stage_in = [&](int st) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) copy_piece(st, q);
         };
 
         const int wave_w = kOperandBytes + (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
@@ -192,10 +197,18 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                 // stages j + 2 ... j + kAhead - 1 (as far as they exist) may stay in flight
                 wait_copies(STEADY ? kAhead - 2 : min(j + kAhead - 1, nk - 1) - (j + 1));
                 asm volatile("s_barrier" ::: "memory");
-                if (STEADY || j + kAhead < nk) stage_in(slot_free);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_pair<0>(fr.w[C], fr.x[0], acc);
+            // the four copies of stage j + kAhead are issued between the first MFMAs, whose execution
+            // covers the scalar and address arithmetic of the copies
+            const bool refill = more && (STEADY || j + kAhead < nk);
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf) {
+                __builtin_amdgcn_sched_barrier(0);
+                acc[nf][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.w[C][nf], fr.x[0][0], acc[nf][0], 0, 0, 0);
+                acc[nf][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fr.w[C][nf], fr.x[0][1], acc[nf][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (refill) copy_piece(slot_free, nf);
+            }
             __builtin_amdgcn_sched_barrier(0);
             lds_read_x(fr.x[3], cur + wave_x, 3);
             if (more) {
@@ -216,7 +229,11 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             slot = slot_next;
         };
 
-        __syncthreads();                 // every wavefront is done reading the previous unit's stages
+        // Every wavefront is done reading the previous unit's stages (its MFMAs have consumed them).  A
+        // bare barrier: the previous unit's output stores need not have completed, they drain while this
+        // unit starts (they count in vmcnt like the copies, so the first waits below may also wait for
+        // them: never too short, since no more than the given number of operations stays outstanding).
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
         for (int sidx = 0; sidx < kAhead; ++sidx)
             if (sidx < nk) stage_in(sidx);
