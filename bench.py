@@ -61,12 +61,13 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once csrc/ffn.hip or csrc/ffn_tile.hip has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "11762ead3235f275", "ffn_tile.hip": "8b4aa9239f9c871f"}
+TRAFFIC_SOURCES = {"ffn.hip": "e0492cdfc9b5c694", "ffn_tile.hip": "119ba9a20cf838ce",
+                   "tile_schedule.hpp": "8a4d4f29b755ce28"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316160331, ("switch_base", "stream_w2"): 321546923,
-    ("nllb_decode", "stream_w1"): 1645870453, ("nllb_decode", "stream_w2"): 1644655102,
-    ("nllb_prefill_skew", "stream_w1"): 1121994617, ("nllb_prefill_skew", "stream_w2"): 1121810504,
-    ("nllb_prefill_skew", "tile_w1"): 2622958568, ("nllb_prefill_skew", "tile_w2"): 2360217660,
+    ("switch_base", "stream_w1"): 316223251, ("switch_base", "stream_w2"): 321698528,
+    ("nllb_decode", "stream_w1"): 1645959189, ("nllb_decode", "stream_w2"): 1646904569,
+    ("nllb_prefill_skew", "stream_w1"): 1158712013, ("nllb_prefill_skew", "stream_w2"): 1152602590,
+    ("nllb_prefill_skew", "tile_w1"): 2505389519, ("nllb_prefill_skew", "tile_w2"): 2218296642,
 }
 
 

@@ -114,7 +114,7 @@ moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, offsets, mask, y_perm, at<void>(ws, L.h),
                                       at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big), at<int32_t>(ws, L.ntiles),
-                                      at<float>(ws, L.partials), static_cast<hipStream_t>(stream)));
+                                      at<float>(ws, L.partials), at<void>(ws, L.x_kmajor), static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_t* inv_perm,

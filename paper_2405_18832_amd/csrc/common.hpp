@@ -199,7 +199,7 @@ hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm,
                              void* h_ws, Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
-                             hipStream_t st);
+                             void* x_kmajor_ws, hipStream_t st);
 hipError_t launch_combine(const moe_shape& s, const float* y_perm, const int32_t* inv_perm,
                           const int32_t* idx, const float* gate, const uint8_t* mask, void* out,
                           hipStream_t st);

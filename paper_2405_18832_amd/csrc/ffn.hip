@@ -471,11 +471,16 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
                              Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
-                             hipStream_t st) {
+                             void* x_kmajor_ws, hipStream_t st) {
     const TileLists lists = ffn_tile_lists(s, tiles_ws, tiles_big_ws, ntiles_ws, partials_ws);
     hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, mask, s.E, s.T * s.k, lists);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
+    if (layer_gathers_kmajor(s)) {      // large layer: re-lay the permuted rows k-step-major first
+        err = launch_gather_kmajor(s, x_perm, nullptr, x_kmajor_ws, st);
+        if (err != hipSuccess) return err;
+        return launch_expert_products(s, x_kmajor_ws, nullptr, true, w1, w2, y_perm, h_ws, lists, st);
+    }
     return launch_expert_products(s, x_perm, nullptr, false, w1, w2, y_perm, h_ws, lists, st);
 }
 

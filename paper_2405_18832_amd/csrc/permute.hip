@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const V* __restrict__ 
 }
 
 // gather into the k-step-major layout of the products' row operand: xk[kb][p][0..31] =
-// x[tokmap[p]][32 kb ... 32 kb + 31].  One thread per 16 bytes of the destination, which is written
+// x[tokmap[p]][32 kb ... 32 kb + 31] (tokmap may be NULL: identity).  One thread per 16 bytes of the destination, which is written
 // contiguously; every token row is read in 64-byte pieces.
 __global__ __launch_bounds__(256) void gather_kmajor_kernel(const uint4* __restrict__ x,
                                                             const int32_t* __restrict__ tokmap,
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void gather_kmajor_kernel(const uint4* __restr
     const int c = static_cast<int>(i & 3);
     const size_t pr = i >> 2;                           // kb * A + p
     const int p = static_cast<int>(pr % A), kb = static_cast<int>(pr / A);
-    const int t = min(max(tokmap[p], 0), T - 1);
+    const int t = tokmap ? min(max(tokmap[p], 0), T - 1) : p;   // no map: x already has the A rows in order
     xk[i] = x[static_cast<size_t>(t) * row_vecs + kb * 4 + c];
 }
 
