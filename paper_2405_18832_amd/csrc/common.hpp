@@ -68,6 +68,29 @@ __device__ __forceinline__ size_t h_index(int row, int n, int rows_total) {
 }
 #endif
 
+#ifdef __HIPCC__
+typedef const void __attribute__((address_space(1))) * gptr_t;
+typedef void __attribute__((address_space(3))) * lptr_t;
+
+// byte address inside LDS of a pointer to __shared__ memory
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return static_cast<uint32_t>(reinterpret_cast<size_t>((lptr_t)(p)));
+}
+
+// 16 bytes per lane from global memory straight into LDS at `lds_base + 16 * lane` (no registers);
+// `lds_base` (an LDS byte address) is the same for the whole wavefront and goes into M0.  Written as inline assembly: after the
+// compiler's own builtin for this instruction it makes every later wait for an LDS read a wait for all
+// outstanding LDS reads (as long as a copy is in flight, which here is always), and the loops that
+// use it depend on waiting only for the oldest ones.  The copies are counted by vmcnt; the code waits for
+// them explicitly, and orders them against LDS reads with barriers.  M0 is not live across statements
+// in compiled code for this target (the compiler sets it right before each use of its own).
+__device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory");
+}
+
+#endif
+
 struct TileLists {
     Tile* small_tiles;     // capacity A / small_rows + E
     Tile* big_tiles;       // capacity A / kBigTileRows + E (unused when big_min == 0)

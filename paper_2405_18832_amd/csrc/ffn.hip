@@ -100,6 +100,14 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 #ifndef MOE_PF_TF4
 #define MOE_PF_TF4 3      // ... tiles of <= 64 rows
 #endif
+#ifndef MOE_PF_LDS
+#define MOE_PF_LDS 6      // k-steps of weight loads in flight when the rows come from LDS
+#endif
+
+// s_waitcnt immediate that waits for vmcnt <= n only (n < 64: low four bits in [3:0], the rest in [15:14])
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+constexpr size_t kStreamRowLdsMax = 128 * 1024;   // largest row tile kept in LDS by the streaming kernel
 
 template <int TFC> struct StreamPF;
 template <> struct StreamPF<1> { static constexpr int value = MOE_PF_TF1; };
@@ -218,6 +226,112 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     if (KSPLIT > 1) __syncthreads();
 }
 
+// The same unit when all four wavefronts of the block share the tile's rows over the same k range
+// (KSPLIT = 1: the block covers four column groups): the rows are copied once per block into LDS, in
+// MFMA-fragment order, instead of being fetched by every wavefront at every k-step.  That takes the
+// row operand out of the vector-memory queue that the weights stream through (one quarter of the
+// requests, issued once, asynchronously) and out of the registers that hold loads in flight.
+// `tok_lds` holds TFC * K / 32 fragments of 1 KiB: fragment (tf, kb) at (tf * K / 32 + kb) * 1024.
+template <int TFC, bool FIRST>
+__device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act,
+                                                const int32_t* __restrict__ rowmap,
+                                                const uint16_t* __restrict__ wpk, void* __restrict__ outp,
+                                                const Tile tl, const int ng, const bool active, const int N,
+                                                const int K, const int rows_total, const bool act_kmajor,
+                                                unsigned char* tok_lds) {
+    constexpr int PF = MOE_PF_LDS;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+    const int nblk = N >> 4, kblk = K >> 5;
+    f32x4 acc[4][TFC];
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+        for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // every wavefront has finished reading the previous unit's rows
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // rows -> LDS: wavefront w copies the fragments (tf, kb) with kb = w, w + 4, ...; a lane fetches the
+    // 16 bytes of its own slot: row (lane % 16), k-group (lane / 16)
+    const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+    const uint32_t lds0 = lds_address(tok_lds);
+#pragma unroll
+    for (int tf = 0; tf < TFC; ++tf) {
+        int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+        if (rowmap != nullptr) row = rowmap[row];
+        const uint16_t* ap =
+            act_kmajor ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
+        for (int kb = wave; kb < kblk; kb += 4) copy16_to_lds(ap + kb * kstride, lds0 + (tf * kblk + kb) * 1024);
+    }
+
+    const uint16_t* wp[4];
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf) {
+        const int nb = min(ng * 4 + nf, nblk - 1);
+        wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
+    }
+    bf16x8 a[PF][4];
+    auto issue = [&](int slot, int kb) {
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf)
+            a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
+    };
+    if (active) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) issue(p, min(p, kblk - 1));   // past the end: re-read, never used
+    }
+    // The row copies were issued before the weight loads, and loads complete in order: they have landed
+    // once at most the weight loads are outstanding ... for every wavefront.
+    if (active) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PF * 4));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("s_barrier" ::: "memory");
+
+    if (active) {
+        const unsigned char* bl = tok_lds + lane * 16;
+        auto fma = [&](int slot, int kb) {
+            bf16x8 b[TFC];
+#pragma unroll
+            for (int tf = 0; tf < TFC; ++tf) b[tf] = *reinterpret_cast<const bf16x8*>(bl + (tf * kblk + kb) * 1024);
+#pragma unroll
+            for (int tf = 0; tf < TFC; ++tf)
+#pragma unroll
+                for (int nf = 0; nf < 4; ++nf)
+                    acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[tf], acc[nf][tf], 0, 0, 0);
+        };
+        int kb = 0;
+        for (; kb + 2 * PF <= kblk; kb += PF) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                fma(p, kb + p);
+                issue(p, kb + p + PF);
+            }
+        }
+        if (kb + PF < kblk) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                fma(p, kb + p);
+                issue(p, min(kb + p + PF, kblk - 1));
+            }
+            kb += PF;
+        }
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+            if (kb + p < kblk) fma(p, kb + p);
+
+#pragma unroll
+        for (int tf = 0; tf < TFC; ++tf) {
+            const int lr = tf * 16 + r;
+            if (lr >= tl.rows) continue;
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf) {
+                const int nb = ng * 4 + nf;
+                if (nb >= nblk) continue;
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+            }
+        }
+    }
+}
+
 template <int TFMAX, int KSPLIT, bool FIRST>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
                                                          const int32_t* __restrict__ rowmap,
@@ -228,7 +342,8 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
-                                                         int rows_total, int act_kmajor) {
+                                                         int rows_total, int act_kmajor, int rows_in_lds) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
     if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total);
@@ -263,6 +378,18 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         const int ng = (bu % ngchunks) * NGB + ngs;
         const bool active = ng < ngroups;                 // wave-uniform
         const int tfc = (tl.rows + 15) >> 4;              // token fragments in use: block-uniform
+        if (KSPLIT == 1 && rows_in_lds) {
+            const bool km = act_kmajor != 0;
+            if (TFMAX >= 4 && tfc == 4)
+                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+            else if (TFMAX >= 4 && tfc == 3)
+                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+            else if (TFMAX >= 2 && tfc == 2)
+                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+            else
+                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+            continue;
+        }
         if (TFMAX >= 4 && tfc == 4)
             stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else if (TFMAX >= 4 && tfc == 3)
@@ -329,12 +456,28 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 256, 0) != hipSuccess || n <= 0) n = 1;
         per_cu = n;
     }
-    long grid = static_cast<long>(device_cu_count()) * per_cu;
+    // KSPLIT = 1: the tile's rows (16 * TFMAX x K, bf16) go through LDS when they fit
+    const size_t row_bytes = static_cast<size_t>(16) * TFMAX * K * 2;
+    const bool rows_in_lds = KSPLIT == 1 && row_bytes <= kStreamRowLdsMax;
+    const size_t lds = rows_in_lds ? row_bytes : 0;
+    static size_t lds_allowed = 48 * 1024;
+    if (lds > lds_allowed) {
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStreamRowLdsMax));
+        if (ea != hipSuccess) return ea;
+        lds_allowed = kStreamRowLdsMax;
+    }
+    int blocks_per_cu = per_cu;
+    if (lds > 0 &&
+        (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, kern, 256, lds) != hipSuccess || blocks_per_cu <= 0))
+        blocks_per_cu = 1;
+    long grid = static_cast<long>(device_cu_count()) * blocks_per_cu;
     if (grid > max_units && partials == nullptr) grid = max_units;   // with partial tiles to add: all blocks
     if (grid < 1) grid = 1;
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total, act_kmajor ? 1 : 0);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), lds, st, act, rowmap, wpk, outp, tiles,
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total,
+                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0);
     return hipGetLastError();
 }
 

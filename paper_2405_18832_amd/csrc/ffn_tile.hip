@@ -30,21 +30,6 @@ constexpr int kAhead = kStages - 1; // the iteration for stage j issues the copi
 constexpr int kOperandBytes = kTM * kTK * 2;        // 16 KiB per operand per stage
 constexpr int kStageBytes = 2 * kOperandBytes;      // 32 KiB per stage
 
-typedef const void __attribute__((address_space(1))) * gptr_t;
-typedef void __attribute__((address_space(3))) * lptr_t;
-
-// 16 bytes per lane from global memory straight into LDS at `lds_base + 16 * lane` (no registers);
-// `lds_base` (an LDS byte address) is the same for the whole wavefront and goes into M0.  Written as inline assembly: after the
-// compiler's own builtin for this instruction it makes every later wait for an LDS read a wait for all
-// outstanding LDS reads (as long as a copy is in flight, which here is always), and the loop below
-// depends on waiting only for the oldest ones.  The copies are counted by vmcnt; the code waits for
-// them explicitly, and orders them against LDS reads with barriers.  M0 is not live across statements
-// in compiled code for this target (the compiler sets it right before each use of its own).
-__device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
-    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory");
-}
-
 // Wait until at most `stages` stages' worth of this wavefront's copies (4 each) are still in flight.
 __device__ __forceinline__ void wait_copies(int stages) {
     if (stages >= 3) __builtin_amdgcn_s_waitcnt(0x0F7C);         // vmcnt(12)
@@ -101,7 +86,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
     const int ntn = (N + kTN - 1) / kTN;
     const int ntiles = ntiles_p[0];
     // LDS byte address of the first of the two fragments that this wavefront copies in, stage 0
-    const uint32_t copy_base = static_cast<uint32_t>(reinterpret_cast<size_t>((lptr_t)smem)) + 2 * wave * 1024;
+    const uint32_t copy_base = lds_address(smem) + 2 * wave * 1024;
 
     // Blocks are handed to the 8 XCDs round-robin, and each XCD has its own L2: block b takes position pb
     // of a round, so that the blocks of one XCD hold G / 8 consecutive units, a GM x GN patch whose
