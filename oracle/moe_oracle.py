@@ -154,6 +154,19 @@ def hot_mask_top_h(counts, H):
     return mask
 
 
+def hot_expert_count(counts, alpha, bw_a, bw_b):
+    """H of the load-balancing rule (Section 3.3, Eq. 3-6): the two workflows are bound by the
+    bandwidth that feeds them, t_a = Expert_a / BW_a and t_b = Expert_b / BW_b with
+    Expert_a + Expert_b = Expert_Activ (the experts with at least one token); equal runtimes give
+    Expert_a = BW_a / (BW_a + BW_b) * Expert_Activ, and H = alpha * Expert_a with the tuning
+    factor alpha.  The paper does not say how the real number becomes a count: it is rounded to the
+    nearest integer, halves up, and clipped to [0, E]."""
+    E = int(np.asarray(counts).shape[0])
+    activ = activated_experts(counts)
+    h = float(alpha) * float(bw_a) / (float(bw_a) + float(bw_b)) * float(activ)
+    return max(0, min(int(np.floor(h + 0.5)), E))
+
+
 def round_bf16(a):
     """Round fp64 values to the nearest bfloat16 (8 significant bits, ties to even),
     returned as fp64.  Written from the format's definition (sign, 8 exponent bits,

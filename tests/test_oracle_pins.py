@@ -163,6 +163,28 @@ def test_hot_mask_top_h():
 
 
 # ---------------------------------------------------------------- special cases
+def test_hot_expert_count_eq6():
+    # values worked out by hand from Eq. 6 (tests/golden/hot_count_examples.json)
+    with open(os.path.join(GOLD, "hot_count_examples.json")) as fh:
+        cases = json.load(fh)["cases"]
+    for c in cases:
+        assert orc.activated_experts(c["counts"]) == c["activ"]
+        assert orc.hot_expert_count(c["counts"], c["alpha"], c["bw_a"], c["bw_b"]) == c["H"]
+    # the rule's purpose (Eq. 3-5): with alpha = 1 the two bandwidth-bound runtimes H / BW_a and
+    # (Expert_Activ - H) / BW_b are equal up to the rounding of H, i.e. H is within 1/2 of the real solution
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        E = int(rng.integers(1, 200))
+        counts = rng.integers(0, 4, E)
+        a, b = float(rng.uniform(1, 100)), float(rng.uniform(1, 1000))
+        H = orc.hot_expert_count(counts, 1.0, a, b)
+        activ = int((counts > 0).sum())
+        assert abs(H * (a + b) - a * activ) <= 0.5 * (a + b) * (1 + 1e-12)
+        assert 0 <= H <= activ
+    # alpha scales the real-valued solution before rounding
+    assert orc.hot_expert_count([1] * 90, 2.0, 1.0, 8.0) == 20
+
+
 def test_single_expert_is_a_plain_ffn():
     x, wg, b, W1, W2 = tiny(T=7, E=1, k=1, bias=True)
     ref = torch.relu(torch.from_numpy(x) @ torch.from_numpy(W1[0]).T) @ torch.from_numpy(W2[0]).T
