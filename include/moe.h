@@ -105,6 +105,22 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Hot-set size of the load-balancing rule (Section 3.3, Eq. 3-6) and the hot mask it implies.
+ * The hot workflow is fed at bandwidth bw_a, the cold one at bw_b (any common unit); both are
+ * bound by moving expert parameters, so equal runtimes put bw_a / (bw_a + bw_b) of the activated
+ * experts (those with at least one token) on the hot side; alpha is the paper's tuning factor:
+ *   H = alpha * bw_a / (bw_a + bw_b) * #{e : counts[e] > 0},
+ * evaluated in double precision in this order, rounded to the nearest integer with halves up and
+ * clipped to [0, E] (the paper leaves the rounding open).
+ *   counts [E] device, as written by moe_route; H_out: device int32 (may be NULL);
+ *   hot_mask [E] device (may be NULL): 1 for the H experts with the largest counts, equal counts
+ *   ordered by lowest index -- the mask moe_expert_ffn / moe_combine / moe_layer_forward take.
+ * alpha >= 0, bw_a > 0, bw_b >= 0, all finite, else MOE_ERR_INVALID_ARG.  One small kernel on `stream`.
+ */
+moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double alpha, double bw_a,
+                          double bw_b, int32_t* H_out, uint8_t* hot_mask, void* stream);
+
+/*
  * Dispatch (Section 2.1 "route each token to the top-k experts"; Section 4.1: drop-less,
  * padding-less).  Stable counting sort of the A assignments by expert:
  *   perm [A]: perm[p] = flat assignment id at sorted position p (experts ascending, inside

@@ -22,7 +22,7 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 
 EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
-           "moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]
+           "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]
 
 
 class MoEError(RuntimeError):
@@ -67,6 +67,8 @@ def load() -> ctypes.CDLL:
     lib.moe_route.restype = ctypes.c_int
     lib.moe_route.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.moe_permute.restype = ctypes.c_int
+    lib.moe_select_hot.argtypes = [sp, vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, vp, vp, vp]
+    lib.moe_select_hot.restype = ctypes.c_int
     lib.moe_permute.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_expert_ffn.restype = ctypes.c_int
     lib.moe_expert_ffn.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -147,6 +149,11 @@ def moe_route(shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, off
     _check(load().moe_route(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(topk_idx),
                             _ptr(topk_w), _ptr(margin), _ptr(counts), _ptr(offsets), int(H), _ptr(hot_mask),
                             _ptr(ws), _nbytes(ws), _stream(stream)), "moe_route")
+
+
+def moe_select_hot(shape, counts, alpha, bw_a, bw_b, H_out, hot_mask, stream=None) -> None:
+    _check(load().moe_select_hot(ctypes.byref(shape), _ptr(counts), float(alpha), float(bw_a), float(bw_b),
+                                 _ptr(H_out), _ptr(hot_mask), _stream(stream)), "moe_select_hot")
 
 
 def moe_permute(shape, x, topk_idx, offsets, perm, inv_perm, x_perm, ws, stream=None) -> None:

@@ -1,5 +1,7 @@
 // C ABI of the MoE FFN library: argument validation on the host, then asynchronous kernel
 // launches on the caller's stream.  No entry point allocates, synchronises or copies to the host.
+#include <cmath>
+
 #include "common.hpp"
 
 using namespace moe;
@@ -84,6 +86,17 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, 
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_route(*shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, offsets, H,
                                  hot_mask, at<int32_t>(ws, L.hist), static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double alpha, double bw_a, double bw_b,
+                          int32_t* H_out, uint8_t* hot_mask, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (counts == nullptr) return MOE_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0) || !(bw_a > 0.0) || !(bw_b >= 0.0) || std::isinf(alpha) || std::isinf(bw_a) || std::isinf(bw_b))
+        return MOE_ERR_INVALID_ARG;
+    return from_hip(launch_select_hot(shape->E, counts, alpha, bw_a, bw_b, H_out, hot_mask,
+                                      static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* topk_idx, const int32_t* offsets,

@@ -199,6 +199,8 @@ hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, c
                         int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws,
                         hipStream_t st);
 int route_chunk_tokens(const moe_shape& s);
+hipError_t launch_select_hot(int E, const int32_t* counts, double alpha, double bw_a, double bw_b, int32_t* H_out,
+                             uint8_t* hot_mask, hipStream_t st);
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,

@@ -297,6 +297,38 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     emit_tiles(e, row0, on ? mine : 0, lists, scan);
 }
 
+// Hot-set size from the counts (Section 3.3, Eq. 6) and the top-H mask.  One block, thread e owns
+// expert e.  The real-valued H is formed in double precision with individually rounded operations
+// (no fused multiply-add), so that it is the same number a plain double evaluation gives.
+__global__ __launch_bounds__(1024) void select_hot_kernel(const int32_t* __restrict__ counts, int E, double alpha,
+                                                          double bw_a, double bw_b, int32_t* __restrict__ H_out,
+                                                          uint8_t* __restrict__ hot_mask) {
+    __shared__ int32_t cnt[MOE_MAX_E];
+    __shared__ int32_t active;
+    const int e = threadIdx.x;
+    if (e == 0) active = 0;
+    const int mine = e < E ? counts[e] : 0;
+    cnt[e] = mine;
+    __syncthreads();
+    if (e < E && mine > 0) atomicAdd(&active, 1);
+    __syncthreads();
+    const double share = __ddiv_rn(__dmul_rn(alpha, bw_a), __dadd_rn(bw_a, bw_b));
+    const double h = floor(__dadd_rn(__dmul_rn(share, static_cast<double>(active)), 0.5));
+    const int H = h >= static_cast<double>(E) ? E : (h <= 0.0 ? 0 : static_cast<int>(h));
+    if (e == 0 && H_out != nullptr) *H_out = H;
+    if (e < E && hot_mask != nullptr) {
+        int rank = 0;
+        for (int o = 0; o < E; ++o) rank += (cnt[o] > mine || (cnt[o] == mine && o < e)) ? 1 : 0;
+        hot_mask[e] = rank < H ? 1 : 0;
+    }
+}
+
+hipError_t launch_select_hot(int E, const int32_t* counts, double alpha, double bw_a, double bw_b, int32_t* H_out,
+                             uint8_t* hot_mask, hipStream_t st) {
+    hipLaunchKernelGGL(select_hot_kernel, dim3(1), dim3(1024), 0, st, counts, E, alpha, bw_a, bw_b, H_out, hot_mask);
+    return hipGetLastError();
+}
+
 __global__ void mask_out_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int E) {
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e < E) dst[e] = src ? (src[e] ? 1 : 0) : 1;

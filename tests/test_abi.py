@@ -20,7 +20,7 @@ def declared_functions():
 def test_header_and_binding_agree():
     names = declared_functions()
     assert sorted(moe.EXPORTS) == names
-    for n in ["moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
+    for n in ["moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
         assert n in names and callable(getattr(moe, n))
 
 
@@ -96,6 +96,10 @@ def test_bad_pointers_and_workspace_are_rejected():
     assert lib.moe_pack_weights(ctypes.byref(s), 3, FAKE, FAKE + 256, None) == moe.MOE_ERR_INVALID_ARG
     assert lib.moe_pack_weights(ctypes.byref(s), 1, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
     assert lib.moe_route(None, FAKE, FAKE, None, FAKE, FAKE, None, FAKE, FAKE, -1, None, FAKE, n, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_select_hot(ctypes.byref(s), None, 1.0, 1.0, 1.0, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_select_hot(ctypes.byref(s), FAKE, -1.0, 1.0, 1.0, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_select_hot(ctypes.byref(s), FAKE, 1.0, 0.0, 1.0, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_select_hot(ctypes.byref(s), FAKE, 1.0, 1.0, float("nan"), FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
 
 
 def test_binding_raises_on_error():

@@ -358,6 +358,40 @@ def test_layer_forward(gpu_lib, name):
     assert torch.equal(a.view(torch.uint8), L.out.view(torch.uint8))
 
 
+# ------------------------------------------------------------------------------ hot-set size (Eq. 6)
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["tiny_f32", "many_experts", "max_experts", "switch_large_skew", "nllb_decode",
+                                  "nllb_prefill_skew"])
+def test_select_hot(gpu_lib, name):
+    """H and the hot mask from the device counts, against the oracle's Eq. 6: integers, so bit-exact (both sides
+    form the real-valued H in double precision, same order of operations)."""
+    cfg = CFG(name)
+    say(f"[case] moe_select_hot {name}")
+    r = oracle_route(name)
+    counts = np.asarray(r["counts"])
+    dev = torch.device("cuda:0")
+    s = gpu_lib.make_shape(T=cfg.T, d_model=cfg.d_model, d_ff=cfg.d_ff, E=cfg.E, k=cfg.k, dtype=cfg.dtype,
+                           renormalize=cfg.renormalize)
+    rng = np.random.default_rng(3)
+    cases = [(1.0, 64.0, 512.0), (1.5, 64.0, 512.0), (1.0, 1.0, 1.0), (0.0, 2.0, 3.0), (50.0, 5.0, 1.0),
+             (1.0, 8000.0, 0.0)]
+    cases += [(float(rng.uniform(0, 3)), float(rng.uniform(1, 100)), float(rng.uniform(0, 1000))) for _ in range(20)]
+    variants = [counts, np.zeros_like(counts), np.ones_like(counts), counts[::-1].copy()]
+    for cv in variants:
+        cd = torch.from_numpy(cv.astype(np.int32)).to(dev)
+        for alpha, a, b in cases:
+            H_out = torch.full((1,), -7, dtype=torch.int32, device=dev)
+            mask = torch.full((cfg.E,), 9, dtype=torch.uint8, device=dev)
+            gpu_lib.moe_select_hot(s, cd, alpha, a, b, H_out, mask)
+            torch.cuda.synchronize()
+            H_ref = orc.hot_expert_count(cv, alpha, a, b)
+            assert int(H_out.item()) == H_ref, (alpha, a, b)
+            assert np.array_equal(mask.cpu().numpy(), orc.hot_mask_top_h(cv, H_ref)), (alpha, a, b)
+    # either output may be omitted
+    gpu_lib.moe_select_hot(s, torch.from_numpy(counts.astype(np.int32)).to(dev), 1.0, 1.0, 1.0, None, None)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------------------ degenerate inputs
 def test_no_tokens_and_empty_mask(gpu_lib):
     from paper_2405_18832_amd.device_layer import DeviceLayer
