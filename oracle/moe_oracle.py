@@ -178,17 +178,31 @@ def round_bf16(a):
     return np.ldexp(q, e)
 
 
-def expert_ffn(X_e, W1_e, W2_e, h_dtype=None):
-    """Y = relu(X W1^T) W2^T for one expert (Section 2.1: two linear layers with an
-    activation in between; Section 3.4: a gemm with a trailing ReLU, then a gemm).
-    W1_e [f, d], W2_e [d, f]; no biases.
+def gelu(z):
+    """GeLU in its defining form z * Phi(z), Phi the standard normal distribution function:
+    0.5 * z * (1 + erf(z / sqrt(2))).  Section 3.4 names "ReLU or GeLU" as the trailing
+    activation without saying which GeLU; the definition is taken, not the tanh approximation."""
+    from scipy.special import erf
+    z = np.asarray(z, F64)
+    return 0.5 * z * (1.0 + erf(z / np.sqrt(2.0)))
+
+
+def expert_ffn(X_e, W1_e, W2_e, h_dtype=None, activation="relu"):
+    """Y = act(X W1^T) W2^T for one expert (Section 2.1: two linear layers with an
+    activation in between; Section 3.4: a gemm with a trailing ReLU or GeLU, then a gemm).
+    W1_e [f, d], W2_e [d, f]; no biases.  activation = "relu" (default) or "gelu".
 
     h_dtype = None keeps the hidden activation in fp64 (the exact definition).
     h_dtype = "bf16" rounds it once to bfloat16 before the second product, which is
     what a bfloat16 inference run (Section 4.1) stores between the two linear layers;
     all sums stay in fp64."""
     h = np.asarray(X_e, F64) @ np.asarray(W1_e, F64).T
-    h = np.maximum(h, 0.0)
+    if activation == "relu":
+        h = np.maximum(h, 0.0)
+    elif activation == "gelu":
+        h = gelu(h)
+    else:
+        raise ValueError(activation)
     if h_dtype == "bf16":
         h = round_bf16(h)
     elif h_dtype not in (None, "f32", "f64"):
@@ -229,7 +243,7 @@ def route(x, w_gate, b_gate, k, renormalize):
 
 
 def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
-                  return_intermediates=False, h_dtype=None):
+                  return_intermediates=False, h_dtype=None, activation="relu"):
     """Whole MoE FFN layer.  `expert(e)` returns (W1_e, W2_e); it is called only for
     experts that received tokens and are not masked out.  With a mask, only the
     masked-in experts' share of the output is produced (Section 3.3: hot experts
@@ -246,7 +260,7 @@ def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
         if hi == lo or (mask is not None and not mask[e]):
             continue
         W1_e, W2_e = expert(e)
-        y_perm[lo:hi] = expert_ffn(x_perm[lo:hi], W1_e, W2_e, h_dtype)
+        y_perm[lo:hi] = expert_ffn(x_perm[lo:hi], W1_e, W2_e, h_dtype, activation)
     out = combine(y_perm, inv, idx, g, mask)
     if return_intermediates:
         r.update(perm=perm, inv_perm=inv, x_perm=x_perm, y_perm=y_perm, out=out)
@@ -254,7 +268,7 @@ def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
     return out
 
 
-def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None):
+def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None, activation="relu"):
     """Dense definition: run every expert on every token, then keep each token's
     top-k experts, weight and sum.  Tiny inputs only."""
     x = np.asarray(x, F64)
@@ -262,7 +276,7 @@ def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None):
     E = w_gate.shape[0]
     Yall = np.empty((T, E, d), F64)
     for e in range(E):
-        Yall[:, e, :] = expert_ffn(x, W1[e], W2[e])
+        Yall[:, e, :] = expert_ffn(x, W1[e], W2[e], activation=activation)
     L = gate_logits(x, w_gate, b_gate)
     p = softmax_rows(L)
     idx = topk_experts(L, k)

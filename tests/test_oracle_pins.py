@@ -226,6 +226,33 @@ def test_relu_is_applied_between_the_layers():
 
 
 # ---------------------------------------------------------------- metamorphic
+def test_gelu_variant():
+    # the activation itself against a library routine that shares nothing with the oracle ...
+    z = np.linspace(-8, 8, 4001)
+    ref = torch.nn.functional.gelu(torch.from_numpy(z), approximate="none").numpy()
+    assert np.allclose(orc.gelu(z), ref, rtol=1e-13, atol=1e-15)
+    # ... and against what the definition z * Phi(z) fixes: gelu(z) - gelu(-z) = z, gelu(0) = 0, the value at 1
+    # from Phi(1) = 0.8413447460685429 (standard normal table), identity for large z, zero for very negative z
+    assert np.allclose(orc.gelu(z) - orc.gelu(-z), z, atol=1e-14)
+    assert orc.gelu(0.0) == 0.0
+    assert abs(float(orc.gelu(1.0)) - 0.8413447460685429) < 1e-15
+    assert abs(float(orc.gelu(40.0)) - 40.0) < 1e-12 and abs(float(orc.gelu(-40.0))) < 1e-12
+    # the tanh approximation is a different function: a plausible mix-up must not pass
+    approx = torch.nn.functional.gelu(torch.from_numpy(z), approximate="tanh").numpy()
+    assert np.abs(orc.gelu(z) - approx).max() > 1e-4
+    # in the layer: brute force over all experts agrees, and the expert is act(x W1^T) W2^T with torch's matmuls
+    x, wg, b, W1, W2 = tiny(T=9, E=4, k=2, bias=True)
+    out = run(x, wg, b, W1, W2, 2, True, activation="gelu")
+    bf = orc.layer_bruteforce(x, wg, b, W1, W2, 2, True, activation="gelu")
+    assert np.allclose(out, bf, rtol=1e-12, atol=1e-12)
+    xt, w1t, w2t = (torch.from_numpy(a) for a in (x, W1[1], W2[1]))
+    ref = (torch.nn.functional.gelu(xt @ w1t.T, approximate="none") @ w2t.T).numpy()
+    assert np.allclose(orc.expert_ffn(x, W1[1], W2[1], activation="gelu"), ref, rtol=1e-12, atol=1e-12)
+    assert not np.allclose(out, run(x, wg, b, W1, W2, 2, True), atol=1e-3)       # and differs from ReLU
+    with pytest.raises(ValueError):
+        orc.expert_ffn(x, W1[0], W2[0], activation="silu")
+
+
 def test_expert_relabelling_and_token_permutation():
     x, wg, b, W1, W2 = tiny(T=11, E=6, k=2, bias=True, seed=5)
     base = run(x, wg, b, W1, W2, 2, True)
