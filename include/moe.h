@@ -51,11 +51,14 @@ typedef enum {
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 
+/* trailing activation of an expert's first linear layer (Section 3.4: "ReLU or GeLU") */
+typedef enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1 } moe_activation;
+
 typedef struct {
     int32_t T, d_model, d_ff, E, k;
     int32_t dtype;         /* moe_dtype                                              */
     int32_t renormalize;   /* 0: gate = p_e ; 1: gate = p_e / sum of the chosen k p   */
-    int32_t activation;    /* 0 = ReLU (the only value accepted)                     */
+    int32_t activation;    /* moe_activation: 0 = ReLU, 1 = GeLU (z * Phi(z), erf form) */
 } moe_shape;
 
 #define MOE_MAX_K 8

@@ -14,7 +14,7 @@ moe_status check_shape(const moe_shape* s) {
     if (s->k > s->E) return MOE_ERR_INVALID_ARG;
     if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_INVALID_ARG;
     if (s->renormalize != 0 && s->renormalize != 1) return MOE_ERR_INVALID_ARG;
-    if (s->activation != 0) return MOE_ERR_UNSUPPORTED;
+    if (s->activation != MOE_ACT_RELU && s->activation != MOE_ACT_GELU) return MOE_ERR_UNSUPPORTED;
     if (s->k > MOE_MAX_K || s->E > MOE_MAX_E) return MOE_ERR_UNSUPPORTED;
     if (s->dtype == MOE_BF16 && (s->d_model % 32 != 0 || s->d_ff % 32 != 0)) return MOE_ERR_UNSUPPORTED;
     // int32 indexing of assignments and of rows

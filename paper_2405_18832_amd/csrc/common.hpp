@@ -57,6 +57,14 @@ constexpr int kSplitSlots = 256;        // partial tiles in the workspace
 constexpr int kSplitCounter = 2;        // ints [2] and [3] of the `ntiles` array: the part counters of the
                                         // first and of the second product
 
+// trailing activation of the first linear layer (Section 3.4): 0 = ReLU, 1 = GeLU in its defining form
+// z * Phi(z) = 0.5 z (1 + erf(z / sqrt 2))
+#ifdef __HIPCC__
+__device__ __forceinline__ float activate(float z, int act) {
+    return act == MOE_ACT_GELU ? 0.5f * z * (1.f + erff(z * 0.70710678118654752f)) : fmaxf(z, 0.f);
+}
+#endif
+
 // Layout of the bf16 intermediate h = relu(x . W1^T) in the workspace: k-step-major, [d_ff / 32][A][32]
 // (A = T * k rows).  The second product consumes h 32 k at a time: the 32 values of consecutive rows
 // are then 64 bytes apart, so a 16-row MFMA operand fragment is one contiguous KiB and a row tile of a
@@ -216,7 +224,8 @@ bool layer_gathers_kmajor(const moe_shape& s);
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, int rows_total, bool act_kmajor, hipStream_t st);
+                               float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
+                               hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,

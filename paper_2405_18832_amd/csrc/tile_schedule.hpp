@@ -55,14 +55,15 @@ __device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, i
     nt = cg * s.GN + slot % wn;
 }
 
-// 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST: relu, bf16, into the
+// 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST: activation, bf16, into the
 // k-step-major h of `rows_total` rows; else fp32 into row-major y of N columns.
 template <bool FIRST>
-__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const f32x4 v) {
+__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, int act,
+                                          const f32x4 v) {
     if (FIRST) {
         uint2 pk;
-        pk.x = f32_to_bf16(fmaxf(v[0], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[1], 0.f))) << 16);
-        pk.y = f32_to_bf16(fmaxf(v[2], 0.f)) | (static_cast<uint32_t>(f32_to_bf16(fmaxf(v[3], 0.f))) << 16);
+        pk.x = f32_to_bf16(activate(v[0], act)) | (static_cast<uint32_t>(f32_to_bf16(activate(v[1], act))) << 16);
+        pk.y = f32_to_bf16(activate(v[2], act)) | (static_cast<uint32_t>(f32_to_bf16(activate(v[3], act))) << 16);
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total)) = pk;
     } else {
         *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + static_cast<size_t>(row) * N + n) = v;
@@ -74,7 +75,7 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
 template <bool FIRST>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
-                                                   int N, int kblk, int G, int rows_total) {
+                                                   int N, int kblk, int G, int rows_total, int act) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
@@ -92,7 +93,7 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
         f32x4 sum = *reinterpret_cast<const f32x4*>(base);
         for (int p = 1; p < s.split; ++p)
             sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
-        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, sum);
+        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, act, sum);
     }
 }
 #endif

@@ -36,7 +36,8 @@ class DeviceLayer:
         receive tokens and generating all weights on the host would take minutes)."""
         self.cfg = cfg
         self.device = torch.device(device)
-        self.shape = make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.dtype, cfg.renormalize)
+        act = {"relu": 0, "gelu": 1}[getattr(cfg, "activation", "relu")]
+        self.shape = make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k, cfg.dtype, cfg.renormalize, act)
         td = torch_dtype(cfg.dtype)
         self.dtype = td
         T, d, f, E, k = cfg.T, cfg.d_model, cfg.d_ff, cfg.E, cfg.k

@@ -69,7 +69,7 @@ def route_status(s, x=FAKE, wg=FAKE, idx=FAKE, w=FAKE, counts=FAKE, offsets=FAKE
     (dict(d_model=48), moe.MOE_ERR_UNSUPPORTED),        # bf16 needs multiples of 32
     (dict(d_ff=100), moe.MOE_ERR_UNSUPPORTED),
     (dict(T=-1), moe.MOE_ERR_INVALID_ARG),
-    (dict(activation=1), moe.MOE_ERR_UNSUPPORTED),
+    (dict(activation=2), moe.MOE_ERR_UNSUPPORTED),        # 0 = ReLU and 1 = GeLU exist
     (dict(dtype=7), moe.MOE_ERR_INVALID_ARG),
 ])
 def test_bad_shapes_are_rejected(kw, status):

@@ -61,6 +61,16 @@ EXTRA = {
     "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
                                renormalize=False, seed=17, zipf_s=40.0),
     "switch_large_skew_matched": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
+    # GeLU as the trailing activation (Section 3.4): fp32 kernel, streaming kernel (rows in LDS / split
+    # contraction), tiled kernel incl. its K-cut last round
+    "gelu_f32": wl.MoEConfig("gelu_f32", T=64, d_model=64, d_ff=256, E=8, k=2, dtype="f32", renormalize=True,
+                             seed=21, activation="gelu"),
+    "gelu_ragged": wl.MoEConfig("gelu_ragged", T=333, d_model=96, d_ff=160, E=11, k=2, dtype="bf16",
+                                renormalize=False, seed=22, zipf_s=1.0, gate_std=0.3, activation="gelu"),
+    "gelu_wide": wl.MoEConfig("gelu_wide", T=96, d_model=256, d_ff=3072, E=6, k=2, dtype="bf16",
+                              renormalize=True, seed=23, gate_std=0.3, activation="gelu"),
+    "gelu_all_to_one": wl.MoEConfig("gelu_all_to_one", T=700, d_model=2048, d_ff=512, E=8, k=1, dtype="bf16",
+                                    renormalize=False, seed=24, zipf_s=40.0, activation="gelu"),
 }
 
 
@@ -69,7 +79,7 @@ def CFG(name):
 
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
-         "many_experts", "max_experts", "all_to_one"]
+         "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one"]
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched"]
 LARGE = ["nllb_decode", "nllb_prefill_skew"]
 
@@ -199,8 +209,8 @@ def oracle_ffn_rows(r, cfg, rows_by_expert):
     experts = [e for e in range(cfg.E) if r["offsets"][e + 1] > r["offsets"][e]]
     for e, rows in zip(experts, rows_by_expert):
         W1, W2 = expert_cached(cfg.name, e)
-        ref_s.append(orc.expert_ffn(x_perm[rows], W1, W2, hd))
-        ref_x.append(orc.expert_ffn(x_perm[rows], W1, W2, None))
+        ref_s.append(orc.expert_ffn(x_perm[rows], W1, W2, hd, cfg.activation))
+        ref_x.append(orc.expert_ffn(x_perm[rows], W1, W2, None, cfg.activation))
         pos.append(rows)
     return np.concatenate(pos), np.concatenate(ref_s), np.concatenate(ref_x)
 
@@ -278,7 +288,7 @@ def oracle_expert_outputs(r, cfg, tokens, h_dtype):
             need.setdefault(int(r["idx"][t, j]), []).append((ti, t, j))
     for e, lst in sorted(need.items()):
         W1, W2 = expert_cached(cfg.name, e)
-        y = orc.expert_ffn(r["x"][[t for _, t, _ in lst]], W1, W2, h_dtype)
+        y = orc.expert_ffn(r["x"][[t for _, t, _ in lst]], W1, W2, h_dtype, cfg.activation)
         for (ti, t, j), yrow in zip(lst, y):
             ys[ti, j] = yrow
     return ys

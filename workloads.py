@@ -80,6 +80,7 @@ class MoEConfig:
     zipf_s: Optional[float] = None   # gate bias = ln Zipf(s) weights; None = no bias
     H: Optional[int] = None          # hot mask = top-H experts by token count
     gate_std: float = 0.02
+    activation: str = "relu"        # trailing activation of the first linear layer: "relu" | "gelu"
 
     @property
     def A(self) -> int:
