@@ -60,9 +60,21 @@ constexpr int kSplitCounter = 2;        // ints [2] and [3] of the `ntiles` arra
 // trailing activation of the first linear layer (Section 3.4): 0 = ReLU, 1 = GeLU in its defining form
 // z * Phi(z) = 0.5 z (1 + erf(z / sqrt 2))
 #ifdef __HIPCC__
-__device__ __forceinline__ float activate(float z, int act) {
-    return act == MOE_ACT_GELU ? 0.5f * z * (1.f + erff(z * 0.70710678118654752f)) : fmaxf(z, 0.f);
+__device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.f + erff(z * 0.70710678118654752f)); }
+
+__device__ __forceinline__ float activate(float z, int act) { return act == MOE_ACT_GELU ? gelu_erf(z) : fmaxf(z, 0.f); }
+
+// Four values at once, the activation a compile-time constant: the MFMA kernels are instantiated per
+// activation (as a run-time choice in their epilogues it cost the ReLU layers 5-10 % of the kernel).
+template <int ACT>
+__device__ __forceinline__ f32x4 activate4(f32x4 v) {
+    if (ACT == MOE_ACT_GELU) return f32x4{gelu_erf(v[0]), gelu_erf(v[1]), gelu_erf(v[2]), gelu_erf(v[3])};
+    return f32x4{fmaxf(v[0], 0.f), fmaxf(v[1], 0.f), fmaxf(v[2], 0.f), fmaxf(v[3], 0.f)};
 }
+
+// template argument FIRST of the product kernels: 0 = second product, else first product with ...
+constexpr int kFirstRelu = 1;
+constexpr int kFirstGelu = 2;
 #endif
 
 // Layout of the bf16 intermediate h = relu(x . W1^T) in the workspace: k-step-major, [d_ff / 32][A][32]

@@ -116,13 +116,13 @@ template <> struct StreamPF<3> { static constexpr int value = MOE_PF_TF3; };
 template <> struct StreamPF<4> { static constexpr int value = MOE_PF_TF4; };
 
 // One wavefront's share of one unit: 4 n-blocks x TFC token fragments over k-steps [kb0, kb1).
-template <int TFC, int TFMAX, int KSPLIT, bool FIRST>
+template <int TFC, int TFMAX, int KSPLIT, int FIRST>
 __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const int32_t* __restrict__ rowmap,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
                                             const int K, const int kb0, const int kb1, f32x4* red,
-                                            const int rows_total, const bool act_kmajor, const int activation) {
+                                            const int rows_total, const bool act_kmajor) {
     constexpr int PF = StreamPF<TFC>::value;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -142,15 +142,16 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
             const int nb = min(ng * 4 + nf, nblk - 1);
             wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
         }
+        const bool km = FIRST == 0 ? true : act_kmajor;     // the second product always reads h
         const uint16_t* ap[TFC];
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) {
             int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
             // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
-            ap[tf] = act_kmajor ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
+            ap[tf] = km ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
         }
-        const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+        const size_t kstride = km ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
         bf16x8 a[PF][4], b[PF][TFC];
         auto issue = [&](int slot, int kb) {
 #pragma unroll
@@ -198,7 +199,9 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 #pragma unroll
                 for (int tf = 0; tf < TFC; ++tf) dst[(nf * TFMAX + tf) * 64] = acc[nf][tf];
         }
-        __syncthreads();
+        // LDS only: a bare barrier after the LDS writes have completed.  (__syncthreads() also waits for
+        // every outstanding global store, i.e. for the previous unit's output rows: a store latency per unit.)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         if (active && ks == 0) {
 #pragma unroll
             for (int s = 1; s < KSPLIT; ++s) {
@@ -219,11 +222,11 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = ng * 4 + nf;
                 if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, activation, acc[nf][tf]);
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
             }
         }
     }
-    if (KSPLIT > 1) __syncthreads();
+    if (KSPLIT > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // `red` may be reused
 }
 
 // The same unit when all four wavefronts of the block share the tile's rows over the same k range
@@ -232,13 +235,13 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 // row operand out of the vector-memory queue that the weights stream through (one quarter of the
 // requests, issued once, asynchronously) and out of the registers that hold loads in flight.
 // `tok_lds` holds TFC * K / 32 fragments of 1 KiB: fragment (tf, kb) at (tf * K / 32 + kb) * 1024.
-template <int TFC, bool FIRST>
+template <int TFC, int FIRST>
 __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act,
                                                 const int32_t* __restrict__ rowmap,
                                                 const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                                 const Tile tl, const int ng, const bool active, const int N,
                                                 const int K, const int rows_total, const bool act_kmajor,
-                                                const int activation, unsigned char* tok_lds) {
+                                                unsigned char* tok_lds) {
     constexpr int PF = MOE_PF_LDS;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -326,13 +329,13 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = ng * 4 + nf;
                 if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, activation, acc[nf][tf]);
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
             }
         }
     }
 }
 
-template <int TFMAX, int KSPLIT, bool FIRST>
+template <int TFMAX, int KSPLIT, int FIRST>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
                                                          const int32_t* __restrict__ rowmap,
                                                          const uint16_t* __restrict__ wpk,
@@ -342,12 +345,11 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
-                                                         int rows_total, int act_kmajor, int rows_in_lds,
-                                                         int activation) {
+                                                         int rows_total, int act_kmajor, int rows_in_lds) {
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total, activation);
+    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -382,23 +384,23 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         if (KSPLIT == 1 && rows_in_lds) {
             const bool km = act_kmajor != 0;
             if (TFMAX >= 4 && tfc == 4)
-                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, activation, tok_lds);
+                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
             else if (TFMAX >= 4 && tfc == 3)
-                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, activation, tok_lds);
+                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
             else if (TFMAX >= 2 && tfc == 2)
-                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, activation, tok_lds);
+                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
             else
-                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, activation, tok_lds);
+                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
             continue;
         }
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, activation);
+            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, activation);
+            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, activation);
+            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, activation);
+            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
     }
 }
 
@@ -446,11 +448,11 @@ int device_cu_count() {
     return cus[dev];
 }
 
-template <int TFMAX, int KSPLIT, bool FIRST>
+template <int TFMAX, int KSPLIT, int FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
                                 const Tile* big_tiles, const float* partials, int rows_total, bool act_kmajor,
-                                int activation, hipStream_t st) {
+                                hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -479,24 +481,24 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), lds, st, act, rowmap, wpk, outp, tiles,
                        ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total,
-                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0, activation);
+                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0);
     return hipGetLastError();
 }
 
-template <int TFMAX, bool FIRST>
+template <int TFMAX, int FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
-                                  bool act_kmajor, int activation, hipStream_t st) {
+                                  bool act_kmajor, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
         return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                              big_tiles, partials, rows_total, act_kmajor, activation, st);
+                                              big_tiles, partials, rows_total, act_kmajor, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, activation, st);
+                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, st);
     return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, activation, st);
+                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -592,10 +594,14 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
-    switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, s.activation, st); break;
-        case 2: err = launch_stream_k<2, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, s.activation, st); break;
-        default: err = launch_stream_k<4, true>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, s.activation, st); break;
+    const bool gelu = s.activation == MOE_ACT_GELU;
+    switch (ffn_tfmax(s) * 2 + (gelu ? 1 : 0)) {
+        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
@@ -605,9 +611,9 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, s.activation, st); break;
-        case 2: err = launch_stream_k<2, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, s.activation, st); break;
-        default: err = launch_stream_k<4, false>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, s.activation, st); break;
+        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
+        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
+        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);

@@ -55,15 +55,16 @@ __device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, i
     nt = cg * s.GN + slot % wn;
 }
 
-// 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST: activation, bf16, into the
-// k-step-major h of `rows_total` rows; else fp32 into row-major y of N columns.
-template <bool FIRST>
-__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, int act,
-                                          const f32x4 v) {
+// 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST != 0 (first product; the value
+// names the activation, kFirstRelu or kFirstGelu): activation, bf16, into the k-step-major h of `rows_total`
+// rows; FIRST == 0 (second product): fp32 into row-major y of N columns.
+template <int FIRST>
+__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const f32x4 v) {
     if (FIRST) {
+        const f32x4 z = activate4<FIRST == kFirstGelu ? MOE_ACT_GELU : MOE_ACT_RELU>(v);
         uint2 pk;
-        pk.x = f32_to_bf16(activate(v[0], act)) | (static_cast<uint32_t>(f32_to_bf16(activate(v[1], act))) << 16);
-        pk.y = f32_to_bf16(activate(v[2], act)) | (static_cast<uint32_t>(f32_to_bf16(activate(v[3], act))) << 16);
+        pk.x = f32_to_bf16(z[0]) | (static_cast<uint32_t>(f32_to_bf16(z[1])) << 16);
+        pk.y = f32_to_bf16(z[2]) | (static_cast<uint32_t>(f32_to_bf16(z[3])) << 16);
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total)) = pk;
     } else {
         *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + static_cast<size_t>(row) * N + n) = v;
@@ -72,10 +73,10 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
 
 // Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
 // Called by every thread of every block of the following kernel; 4 columns of a row per thread and step.
-template <bool FIRST>
+template <int FIRST>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
-                                                   int N, int kblk, int G, int rows_total, int act) {
+                                                   int N, int kblk, int G, int rows_total) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
@@ -93,7 +94,7 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
         f32x4 sum = *reinterpret_cast<const f32x4*>(base);
         for (int p = 1; p < s.split; ++p)
             sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
-        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, act, sum);
+        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, sum);
     }
 }
 #endif
