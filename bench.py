@@ -60,14 +60,14 @@ class HipEvents:
 
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
-# were taken with: reported as null once csrc/ffn.hip or csrc/ffn_tile.hip has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "e0492cdfc9b5c694", "ffn_tile.hip": "119ba9a20cf838ce",
-                   "tile_schedule.hpp": "8a4d4f29b755ce28"}
+# were taken with: reported as null once one of the sources below has changed.
+TRAFFIC_SOURCES = {"ffn.hip": "2bd41d23e8ecc089", "ffn_tile.hip": "62fa86f8f89b82e0",
+                   "tile_schedule.hpp": "690d74564890de0d"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316223251, ("switch_base", "stream_w2"): 321698528,
-    ("nllb_decode", "stream_w1"): 1645959189, ("nllb_decode", "stream_w2"): 1646904569,
-    ("nllb_prefill_skew", "stream_w1"): 1158712013, ("nllb_prefill_skew", "stream_w2"): 1152602590,
-    ("nllb_prefill_skew", "tile_w1"): 2505389519, ("nllb_prefill_skew", "tile_w2"): 2218296642,
+    ("switch_base", "stream_w1"): 316830029, ("switch_base", "stream_w2"): 322271649,
+    ("nllb_decode", "stream_w1"): 1646335784, ("nllb_decode", "stream_w2"): 1645996665,
+    ("nllb_prefill_skew", "stream_w1"): 1159000258, ("nllb_prefill_skew", "stream_w2"): 1152908202,
+    ("nllb_prefill_skew", "tile_w1"): 2490001793, ("nllb_prefill_skew", "tile_w2"): 2212794780,
 }
 
 
