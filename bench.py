@@ -95,7 +95,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="switch_base",
-                    choices=wl.CONFIG_ORDER + [n + "_matched" for n in ("switch_large_skew", "nllb_prefill_skew")])
+                    choices=wl.CONFIG_ORDER + [n + "_matched" for n in ("switch_large_skew", "nllb_prefill_skew")]
+                    + list(wl.EXTRA_CONFIGS))
     ap.add_argument("--share", default="full", choices=["full", "hot"],
                     help="full layer, or only the top-H hot experts' share (workloads with a hot mask)")
     ap.add_argument("--copies", type=int, default=0,
@@ -115,7 +116,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     name = args.workload
-    cfg = wl.matched_noise(wl.CONFIGS[name[:-8]]) if name.endswith("_matched") else wl.CONFIGS[name]
+    cfg = (wl.matched_noise(wl.CONFIGS[name[:-8]]) if name.endswith("_matched")
+           else wl.CONFIGS.get(name) or wl.EXTRA_CONFIGS[name])
     K, W = args.steps, args.warmup
     es = 2 if cfg.dtype == "bf16" else 4
     log(f"[bench] workload {describe(cfg)}")

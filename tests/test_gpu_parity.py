@@ -75,13 +75,15 @@ EXTRA = {
 
 
 def CFG(name):
-    return wl.CONFIGS[name] if name in wl.CONFIGS else EXTRA[name]
+    if name in wl.CONFIGS:
+        return wl.CONFIGS[name]
+    return wl.EXTRA_CONFIGS[name] if name in wl.EXTRA_CONFIGS else EXTRA[name]
 
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
          "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one"]
-MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched"]
-LARGE = ["nllb_decode", "nllb_prefill_skew"]
+MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128"]
+LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4"]
 
 _layers = {}
 

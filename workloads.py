@@ -104,6 +104,23 @@ CONFIGS = {
 CONFIG_ORDER = ["tiny_f32", "switch_base", "switch_large_skew", "nllb_decode",
                 "nllb_prefill_skew"]
 
+# Further shapes the paper evaluates (Section 5): NLLB-MoE decoder steps at batch sizes 1, 4 and 16
+# (one token per sequence and step), and two Switch variants around the base preset for its
+# sensitivity study (the study's exact d_model / E are only in a figure; these take the base width
+# with 8 and 128 experts).  Same recipe as the presets above.
+EXTRA_CONFIGS = {
+    "nllb_decode_b1": MoEConfig("nllb_decode_b1", T=1, d_model=2048, d_ff=8192, E=128, k=2,
+                                dtype="bf16", renormalize=True, seed=5),
+    "nllb_decode_b4": MoEConfig("nllb_decode_b4", T=4, d_model=2048, d_ff=8192, E=128, k=2,
+                                dtype="bf16", renormalize=True, seed=6),
+    "nllb_decode_b16": MoEConfig("nllb_decode_b16", T=16, d_model=2048, d_ff=8192, E=128, k=2,
+                                 dtype="bf16", renormalize=True, seed=7),
+    "switch_base_8": MoEConfig("switch_base_8", T=2048, d_model=768, d_ff=3072, E=8, k=1,
+                               dtype="bf16", renormalize=False, seed=8),
+    "switch_base_128": MoEConfig("switch_base_128", T=2048, d_model=768, d_ff=3072, E=128, k=1,
+                                 dtype="bf16", renormalize=False, seed=9),
+}
+
 
 def matched_noise(cfg: MoEConfig) -> MoEConfig:
     """Secondary variant of a skewed preset: gate std = 1.28/sqrt(d_model), so the
