@@ -85,7 +85,8 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, 
     if (st != MOE_OK) return st;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_route(*shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, offsets, H,
-                                 hot_mask, at<int32_t>(ws, L.hist), static_cast<hipStream_t>(stream)));
+                                 hot_mask, at<int32_t>(ws, L.hist), at<float>(ws, L.gate_part),
+                                 static_cast<hipStream_t>(stream)));
 }
 
 moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double alpha, double bw_a, double bw_b,
@@ -173,7 +174,7 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
     const int tok = route_chunk_tokens(*shape);
     if (shape->T > 0) {
         nchunks = (shape->T + tok - 1) / tok;
-        e = launch_route_fused(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, hs);
+        e = launch_route_fused(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, at<float>(ws, L.gate_part), hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
     e = launch_scan_finalize(hist, nchunks, shape->E, cnt, offsets, derive ? H : -1, derive ? own_mask : nullptr,

@@ -176,9 +176,12 @@ struct WsLayout {
     size_t y_perm;     // float [A, d]
     size_t partials;   // float [kSplitSlots, 256, 256]  (only when an expert can reach kBigMinRows rows)
     size_t x_kmajor;   // bf16 [d/32, A, 32]  gathered token rows, k-step-major (same condition)
+    size_t gate_part;  // float [kGateSplit, 64, E]  partial gate logits of the small-T routing path (T <= 64)
     size_t total;
 };
 
+constexpr int kSmallRouteTokens = 64;   // up to this many tokens the gate product is cut over many small blocks
+constexpr int kGateSplit = 8;           // ... along the contraction into this many slices
 constexpr int kPermChunk = 256;   // assignments per counting-sort chunk (one wavefront)
 
 inline size_t elem_size(int32_t dtype) { return dtype == MOE_BF16 ? 2 : 4; }
@@ -209,6 +212,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     const bool big = s.dtype == MOE_BF16 && s.T >= kBigMinRows;
     L.partials = take(big ? static_cast<size_t>(kSplitSlots) * kBigTileRows * 256 * 4 : 0);
     L.x_kmajor = take(big ? A * s.d_model * es : 0);
+    L.gate_part = take((s.dtype == MOE_BF16 && s.T <= kSmallRouteTokens) ? static_cast<size_t>(kGateSplit) * kSmallRouteTokens * E * 4 : 0);
     L.total = off;
     return L;
 }
@@ -216,13 +220,14 @@ inline WsLayout ws_layout(const moe_shape& s) {
 // ---- internal launchers (all asynchronous on `st`; return hipSuccess or the launch error)
 hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                         int32_t* idx, float* gate, float* margin, int32_t* counts,
-                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws, float* gate_part_ws,
                         hipStream_t st);
 int route_chunk_tokens(const moe_shape& s);
 hipError_t launch_select_hot(int E, const int32_t* counts, double alpha, double bw_a, double bw_b, int32_t* H_out,
                              uint8_t* hot_mask, hipStream_t st);
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
-                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st);
+                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* gate_part_ws,
+                              hipStream_t st);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
                                 uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st);
 TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws, float* partials_ws);

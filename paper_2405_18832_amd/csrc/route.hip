@@ -386,10 +386,105 @@ static hipError_t launch_route_nf(int nf, const moe_shape& s, const void* x, con
     }
 }
 
+// Few tokens (a decode step): the gate product is one skinny GEMM whose cost is reading the gate weights, and
+// one block per 16 tokens would leave that to one or two CUs.  gate_partial_kernel cuts it into
+// (16 experts) x (1 / kGateSplit of the contraction) x (16 tokens) pieces, one wavefront each, which leave fp32
+// partial logits in the workspace; route_topk_kernel adds the slices in order (plus the bias) and does the
+// softmax / top-k / chunk histogram per 16 tokens as route_fused_kernel does.
+__global__ __launch_bounds__(64) void gate_partial_kernel(const uint16_t* __restrict__ x,
+                                                          const uint16_t* __restrict__ wg,
+                                                          float* __restrict__ part, int T, int d, int E, int Tpad) {
+    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    const int nb = blockIdx.x, ks = blockIdx.y, tf = blockIdx.z;
+    const int ksteps = d >> 5;
+    const int per = (ksteps + kGateSplit - 1) / kGateSplit;
+    const int kb0 = min(ksteps, ks * per), kb1 = min(ksteps, kb0 + per);
+    const uint16_t* xr = x + static_cast<size_t>(min(tf * 16 + r, T - 1)) * d + g * 8;
+    const uint16_t* wr = wg + static_cast<size_t>(min(nb * 16 + r, E - 1)) * d + g * 8;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int PF = 8;
+    for (int kb = kb0; kb < kb1; kb += PF) {
+        bf16x8 a[PF], b[PF];
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int kk = min(kb + p, kb1 - 1);            // past the end: re-read, not used
+            a[p] = *reinterpret_cast<const bf16x8*>(wr + kk * 32);
+            b[p] = *reinterpret_cast<const bf16x8*>(xr + kk * 32);
+        }
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+            if (kb + p < kb1) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[p], b[p], acc, 0, 0, 0);
+    }
+    // lane (r, g): token tf * 16 + r, experts nb * 16 + 4 g + 0..3
+    const int t = tf * 16 + r;
+    float* dst = part + (static_cast<size_t>(ks) * Tpad + t) * E;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = nb * 16 + g * 4 + i;
+        if (t < Tpad && e < E) dst[e] = acc[i];
+    }
+}
+
+__global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ part,
+                                                         const float* __restrict__ bias,
+                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                         float* __restrict__ margin,
+                                                         int32_t* __restrict__ chunk_hist, int T, int E, int k,
+                                                         int renorm, int Tpad) {
+    extern __shared__ float lds[];
+    const int Ep = E + 1;
+    float* L = lds;
+    int32_t* hist = reinterpret_cast<int32_t*>(lds + 16 * Ep);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int t0 = blockIdx.x * 16;
+    for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
+    for (int i = threadIdx.x; i < 16 * E; i += 256) {
+        const int tl = i / E, e = i - tl * E;
+        const int t = min(t0 + tl, Tpad - 1);
+        float s = bias ? bias[e] : 0.f;
+        for (int ks = 0; ks < kGateSplit; ++ks) s += part[(static_cast<size_t>(ks) * Tpad + t) * E + e];   // fixed order
+        L[tl * Ep + e] = s;
+    }
+    __syncthreads();
+    const int grp = lane >> 4, sub = lane & 15;
+    const int tl = wave * 4 + grp;                     // 4 wavefronts x 4 tokens
+    const int t = t0 + tl;
+    const bool live = t < T;
+    const size_t o = static_cast<size_t>(live ? t : 0) * k;
+    topk_from_lds(L + tl * Ep, E, k, renorm, sub, live, topk_idx + o, topk_w + o,
+                  margin ? margin + (live ? t : 0) : nullptr, hist);
+    __syncthreads();
+    const int nchunks = gridDim.x;
+    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(e) * nchunks + blockIdx.x] = hist[e];
+}
+
+static hipError_t launch_route_small(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                                     int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* part,
+                                     hipStream_t st) {
+    const int tfs = (s.T + 15) / 16, Tpad = tfs * 16, nbs = (s.E + 15) / 16;
+    hipLaunchKernelGGL(gate_partial_kernel, dim3(nbs, kGateSplit, tfs), dim3(64), 0, st,
+                       static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_gate), part, s.T, s.d_model, s.E,
+                       Tpad);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const size_t lds = static_cast<size_t>(16) * (s.E + 1) * 4 + static_cast<size_t>(s.E) * 4;
+    if (lds > 48 * 1024) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (err != hipSuccess) return err;
+    }
+    hipLaunchKernelGGL(route_topk_kernel, dim3(tfs), dim3(256), lds, st, part, bias, idx, gate, margin, chunk_hist, s.T,
+                       s.E, s.k, s.renormalize, Tpad);
+    return hipGetLastError();
+}
+
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
-                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
+                              int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* gate_part_ws,
+                              hipStream_t st) {
     if (s.dtype != MOE_BF16)
         return launch_route_inst<float, 1, 4, 1>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    if (s.T <= kSmallRouteTokens && gate_part_ws != nullptr)
+        return launch_route_small(s, x, w_gate, bias, idx, gate, margin, chunk_hist, gate_part_ws, st);
     const RouteCfg c = route_cfg(s);
     if (c.nw == 16) return launch_route_nf<1, 16>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
     if (c.tok == 32) return launch_route_nf<2, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
@@ -406,13 +501,13 @@ hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t
 
 hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                         int32_t* idx, float* gate, float* margin, int32_t* counts,
-                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws, float* gate_part_ws,
                         hipStream_t st) {
     int nchunks = 0;
     if (s.T > 0) {
         const int tok = route_chunk_tokens(s);
         nchunks = (s.T + tok - 1) / tok;
-        hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, st);
+        hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, gate_part_ws, st);
         if (err != hipSuccess) return err;
     }
     return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, st);
