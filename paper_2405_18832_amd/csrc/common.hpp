@@ -121,6 +121,24 @@ struct TileLists {
 };
 
 #ifdef __HIPCC__
+// Inclusive prefix sum over the 1024 threads of a block (thread e contributes v): shuffles inside each
+// wavefront, one LDS round for the 16 wavefront totals.  `tmp` is an LDS array of >= 16 ints; two barriers.
+__device__ __forceinline__ int block_scan_1024(int v, int32_t* tmp) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        const int o = __shfl_up(incl, s);
+        if (lane >= s) incl += o;
+    }
+    __syncthreads();                       // tmp may still be read from a previous call
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += tmp[w];
+    return base + incl;
+}
+
 // Called by all 1024 threads of a block, thread e owning expert e (row0, m rows; m = 0 when the
 // expert is empty or masked out).  `scan` is an LDS array of MOE_MAX_E ints.
 __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLists tl, int32_t* scan) {
@@ -129,17 +147,9 @@ __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLis
         const int rows = pass == 0 ? tl.small_rows : kBigTileRows;
         const bool mine = (pass == 1) == big;
         const int nt = mine ? (m + rows - 1) / rows : 0;
-        __syncthreads();
-        scan[e] = nt;
-        __syncthreads();
-        for (int s = 1; s < MOE_MAX_E; s <<= 1) {
-            const int add = (e >= s) ? scan[e - s] : 0;
-            __syncthreads();
-            scan[e] += add;
-            __syncthreads();
-        }
+        const int incl = block_scan_1024(nt, scan);
         Tile* out = pass == 0 ? tl.small_tiles : tl.big_tiles;
-        const int base = scan[e] - nt;
+        const int base = incl - nt;
         for (int i = 0; i < nt; ++i) {
             Tile t;
             t.expert = e;
@@ -148,7 +158,7 @@ __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLis
             t.pad = 0;
             out[base + i] = t;
         }
-        if (e == MOE_MAX_E - 1) tl.ntiles[pass] = scan[e];
+        if (e == MOE_MAX_E - 1) tl.ntiles[pass] = incl;
         if (pass == 0 && e < 2) tl.ntiles[kSplitCounter + e] = 0;
         if (tl.big_min <= 0 && pass == 0) {      // no large experts possible
             if (e == 0) tl.ntiles[1] = 0;

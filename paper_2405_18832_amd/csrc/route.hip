@@ -270,20 +270,13 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     __syncthreads();
     const int e = threadIdx.x;
     const int mine = (e < E) ? cnt[e] : 0;
-    scan[e] = mine;
-    __syncthreads();
-    for (int s = 1; s < MOE_MAX_E; s <<= 1) {
-        const int add = (e >= s) ? scan[e - s] : 0;
-        __syncthreads();
-        scan[e] += add;
-        __syncthreads();
-    }
-    const int row0 = scan[e] - mine;
+    const int incl = block_scan_1024(mine, scan);
+    const int row0 = incl - mine;
     if (e < E) {
         if (counts) counts[e] = mine;
         if (offsets) offsets[e] = row0;
     }
-    if (e == E - 1 && offsets) offsets[E] = scan[e];
+    if (e == E - 1 && offsets) offsets[E] = incl;
     bool on = e < E;
     if (H >= 0 && e < E) {
         int rank = 0;
