@@ -186,12 +186,16 @@ struct WsLayout {
     size_t y_perm;     // float [A, d]
     size_t partials;   // float [kSplitSlots, 256, 256]  (only when an expert can reach kBigMinRows rows)
     size_t x_kmajor;   // bf16 [d/32, A, 32]  gathered token rows, k-step-major (same condition)
-    size_t gate_part;  // float [kGateSplit, 64, E]  partial gate logits of the small-T routing path (T <= 64)
+    size_t gate_part;  // float [kGateSplit, T rounded up to 16, E]  partial gate logits (layers with route_is_split)
     size_t total;
 };
 
-constexpr int kSmallRouteTokens = 64;   // up to this many tokens the gate product is cut over many small blocks
-constexpr int kGateSplit = 8;           // ... along the contraction into this many slices
+// Layers with few tokens (decode steps) cut the gate product over many one-wavefront blocks and along the
+// contraction into kGateSplit slices (partial logits in the workspace).  Measured: a gain up to 64 tokens
+// (one block per 16 tokens leaves reading the gate weights to a few CUs), none at 2048 tokens.
+constexpr int kGateSplit = 8;
+constexpr int kSplitRouteTokens = 64;
+inline bool route_is_split(const moe_shape& s) { return s.dtype == MOE_BF16 && s.T <= kSplitRouteTokens; }
 constexpr int kPermChunk = 256;   // assignments per counting-sort chunk (one wavefront)
 
 inline size_t elem_size(int32_t dtype) { return dtype == MOE_BF16 ? 2 : 4; }
@@ -222,7 +226,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     const bool big = s.dtype == MOE_BF16 && s.T >= kBigMinRows;
     L.partials = take(big ? static_cast<size_t>(kSplitSlots) * kBigTileRows * 256 * 4 : 0);
     L.x_kmajor = take(big ? A * s.d_model * es : 0);
-    L.gate_part = take((s.dtype == MOE_BF16 && s.T <= kSmallRouteTokens) ? static_cast<size_t>(kGateSplit) * kSmallRouteTokens * E * 4 : 0);
+    L.gate_part = take(route_is_split(s) ? static_cast<size_t>(kGateSplit) * ((s.T + 15) / 16 * 16) * E * 4 : 0);
     L.total = off;
     return L;
 }

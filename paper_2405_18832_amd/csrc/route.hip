@@ -338,6 +338,7 @@ static RouteCfg route_cfg(const moe_shape& s) {
     RouteCfg c{16, 4, 1};
     if (s.dtype != MOE_BF16) return c;
     c.nf = s.E >= 113 ? 8 : (s.E >= 49 ? 4 : (s.E >= 17 ? 2 : 1));
+    if (route_is_split(s)) { c.tok = 16; c.nw = 8; return c; }   // the split path works in chunks of 16 tokens
     if (s.T <= 64) { c.tok = 16; c.nw = 16; c.nf = c.nf > 4 ? 4 : c.nf; }   // few blocks: split the contraction 16 ways
                                                                             // (128 registers per lane: 4 fragments at a time)
     else if (s.T >= 4096 && s.E <= 256) { c.tok = 32; c.nw = 8; }
@@ -476,7 +477,7 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
                               hipStream_t st) {
     if (s.dtype != MOE_BF16)
         return launch_route_inst<float, 1, 4, 1>(s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
-    if (s.T <= kSmallRouteTokens && gate_part_ws != nullptr)
+    if (route_is_split(s) && gate_part_ws != nullptr)
         return launch_route_small(s, x, w_gate, bias, idx, gate, margin, chunk_hist, gate_part_ws, st);
     const RouteCfg c = route_cfg(s);
     if (c.nw == 16) return launch_route_nf<1, 16>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
