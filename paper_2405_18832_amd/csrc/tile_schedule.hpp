@@ -63,8 +63,8 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
     if (FIRST) {
         const f32x4 z = activate4<FIRST == kFirstGelu ? MOE_ACT_GELU : MOE_ACT_RELU>(v);
         uint2 pk;
-        pk.x = f32_to_bf16(z[0]) | (static_cast<uint32_t>(f32_to_bf16(z[1])) << 16);
-        pk.y = f32_to_bf16(z[2]) | (static_cast<uint32_t>(f32_to_bf16(z[3])) << 16);
+        pk.x = pack_bf16x2(z[0], z[1]);
+        pk.y = pack_bf16x2(z[2], z[3]);
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total)) = pk;
     } else {
         *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + static_cast<size_t>(row) * N + n) = v;
