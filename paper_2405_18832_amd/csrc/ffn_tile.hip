@@ -97,67 +97,92 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                 : static_cast<int>(blockIdx.x);
     const int nleft = sch.R * sch.split;                // parts of the left-over units
 
-    for (int it = 0;; ++it) {
-        int u, part = 0;
+    // A unit of work: (row tile mt, column tile nt) over k-steps [kb0, kb0 + nk), whole (nparts == 1) or
+    // one of nparts parts of a left-over unit.
+    struct Unit {
+        int u, part, nparts, nt, kb0, nk;
+        Tile tl;
+        bool valid;
+    };
+    auto unit_at = [&](int it) {
+        Unit w;
+        w.valid = true;
+        w.part = 0;
         if (it < sch.rounds) {
-            u = it * G + pb;
+            w.u = it * G + pb;
+            w.nparts = 1;
         } else {
             // left-over parts go to whichever block is free: a counter hands them out (which block
-            // computes a part has no influence on the result)
+            // computes a part has no influence on the result).  The first word of the ring is free now:
+            // every wavefront that gets past the first barrier has read its last stage.
             __syncthreads();
             if (t == 0) *next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
             __syncthreads();
             const int id = *next_part;
-            if (id >= nleft) break;                     // block-uniform; every block gets here
-            u = sch.rounds * G + id / sch.split;
-            part = id % sch.split;
+            w.valid = id < nleft;                          // block-uniform; every block ends up here
+            w.u = sch.rounds * G + (w.valid ? id / sch.split : 0);
+            w.part = w.valid ? id % sch.split : 0;
+            w.nparts = sch.split;
         }
-        const int nparts = (it < sch.rounds) ? 1 : sch.split;
-        int mt, nt;
-        unit_of(sch, u, mt, nt);
-        const int kb0 = kblk * part / nparts;                // kblk * kMaxSplit fits easily
-        const int kb1 = kblk * (part + 1) / nparts;
-        const int nk = kb1 - kb0;
-        const Tile tl = tiles[mt];
-        // This wavefront stages fragments 2*wave and 2*wave+1 of each operand.  A lane fetches the 16
-        // bytes that belong at its own slot of the fragment: row (lane % 16), k-group (lane / 16).
-        const uint16_t* arow[2];
-        const uint16_t* brow[2];
+        int mt = 0;
+        w.nt = 0;
+        if (w.valid) unit_of(sch, w.u, mt, w.nt);
+        w.kb0 = kblk * w.part / w.nparts;                  // kblk * kMaxSplit fits easily
+        w.nk = kblk * (w.part + 1) / w.nparts - w.kb0;
+        w.tl = tiles[w.valid ? mt : 0];
+        return w;
+    };
+
+    // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance.
+    // This wavefront stages fragments 2*wave and 2*wave+1 of each operand.  A lane fetches the 16
+    // bytes that belong at its own slot of the fragment: row (lane % 16), k-group (lane / 16).
+    const uint16_t* arow[2];
+    const uint16_t* brow[2];
+    const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+    auto copy_piece = [&](int st, int q) {             // q = 0 ... 3: row fragment 0, weight 0, row 1, weight 1
+        const int i = q >> 1;
+        if ((q & 1) == 0) {
+            copy16_to_lds(arow[i], copy_base + st * kStageBytes + i * 1024);
+            arow[i] += kstride;
+        } else {
+            copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
+            brow[i] += 512;
+        }
+    };
+    auto stage_in = [&](int st) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) copy_piece(st, q);
+    };
+    // Point the copies at a unit and start its first stages.  Every wavefront must be done reading the
+    // ring (its MFMAs have consumed the last stage): a bare barrier, so that output stores still in flight
+    // need not complete first.
+    auto start_unit = [&](const Unit& w) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            int row = tl.row0 + min((2 * wave + i) * 16 + r, tl.rows - 1);
+            int row = w.tl.row0 + min((2 * wave + i) * 16 + r, w.tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];
             // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
-            arow[i] = act_kmajor ? act + h_index(row, kb0 * 32 + g * 8, rows_total)
-                                 : act + static_cast<size_t>(row) * K + static_cast<size_t>(kb0) * 32 + g * 8;
-            const int nb = min(nt * 16 + 2 * wave + i, nblk - 1);
-            brow[i] = wpk + ((static_cast<size_t>(tl.expert) * nblk + nb) * kblk + kb0) * 512 + lane * 8;
+            arow[i] = act_kmajor ? act + h_index(row, w.kb0 * 32 + g * 8, rows_total)
+                                 : act + static_cast<size_t>(row) * K + static_cast<size_t>(w.kb0) * 32 + g * 8;
+            const int nb = min(w.nt * 16 + 2 * wave + i, nblk - 1);
+            brow[i] = wpk + ((static_cast<size_t>(w.tl.expert) * nblk + nb) * kblk + w.kb0) * 512 + lane * 8;
         }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int sidx = 0; sidx < kAhead; ++sidx)
+            if (sidx < w.nk) stage_in(sidx);
+    };
 
+    const int wave_w = kOperandBytes + (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
+    Unit cur = unit_at(0);
+    if (cur.valid) start_unit(cur);
+    for (int it = 0; cur.valid; ++it) {
+        const int nk = cur.nk;
         f32x4 acc[4][8];
 #pragma unroll
         for (int nf = 0; nf < 4; ++nf)
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        // 4 copies per wavefront and stage; stages are copied in order, so the pointers just advance
-        const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
-        auto copy_piece = [&](int st, int q) {             // q = 0 ... 3: row fragment 0, weight 0, row 1, weight 1
-            const int i = q >> 1;
-            if ((q & 1) == 0) {
-                copy16_to_lds(arow[i], copy_base + st * kStageBytes + i * 1024);
-                arow[i] += kstride;
-            } else {
-                copy16_to_lds(brow[i], copy_base + st * kStageBytes + kOperandBytes + i * 1024);
-                brow[i] += 512;
-            }
-        };
-        auto stage_in = [&](int st) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) copy_piece(st, q);
-        };
-
-        const int wave_w = kOperandBytes + (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
         StageFrags fr;
         // One stage of 32 k, software-pipelined across stages so that the MFMA pipe never waits for LDS.
         // The iteration for stage j starts by making sure that stage j + 1 has landed for every wavefront
@@ -214,14 +239,9 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             slot = slot_next;
         };
 
-        // Every wavefront is done reading the previous unit's stages (its MFMAs have consumed them).  A
-        // bare barrier: the previous unit's output stores need not have completed, they drain while this
-        // unit starts (they count in vmcnt like the copies, so the first waits below may also wait for
-        // them: never too short, since no more than the given number of operations stays outstanding).
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#pragma unroll
-        for (int sidx = 0; sidx < kAhead; ++sidx)
-            if (sidx < nk) stage_in(sidx);
+        // The first waits may also wait for the previous unit's output stores, which were issued after this
+        // unit's first copies and count in vmcnt like them: never too short, since no more than the given
+        // number of operations stays outstanding and the copies complete in order.
         wait_copies(min(kAhead, nk) - 1);                  // stage 0 has landed ...
         asm volatile("s_barrier" ::: "memory");           // ... for every wavefront
         lds_read_w(fr.w[0], smem + wave_w);
@@ -240,29 +260,35 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         if (j + 3 < nk) iterate(std::integral_constant<int, 1>{}, std::false_type{}, j + 3);
         if (j + 4 < nk) iterate(std::integral_constant<int, 0>{}, std::false_type{}, j + 4);
 
+        // The next unit's first copies go out before this unit's output is stored: the copies' latency and
+        // the stores overlap, and the load of the next tile's descriptor does not wait behind the stores.
+        const Unit nxt = unit_at(it + 1);
+        if (nxt.valid) start_unit(nxt);
+
         // Lane holds 4 consecutive columns of one row per accumulator.
-        if (nparts > 1) {
+        if (cur.nparts > 1) {
             // part of a unit: the partial tile goes to the workspace; the next kernel adds the parts up
-            float* mine = partials + (static_cast<size_t>(u - sch.rounds * G) * nparts + part) * (kTM * kTN);
+            float* mine = partials + (static_cast<size_t>(cur.u - sch.rounds * G) * cur.nparts + cur.part) * (kTM * kTN);
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf)
 #pragma unroll
                 for (int nf = 0; nf < 4; ++nf)
                     *reinterpret_cast<f32x4*>(mine + (wm * 128 + tf * 16 + r) * kTN + (wn * 4 + nf) * 16 + g * 4) =
                         acc[nf][tf];
-            continue;
-        }
+        } else {
 #pragma unroll
-        for (int tf = 0; tf < 8; ++tf) {
-            const int lr = wm * 128 + tf * 16 + r;
-            if (lr >= tl.rows) continue;
+            for (int tf = 0; tf < 8; ++tf) {
+                const int lr = wm * 128 + tf * 16 + r;
+                if (lr >= cur.tl.rows) continue;
 #pragma unroll
-            for (int nf = 0; nf < 4; ++nf) {
-                const int nb = nt * 16 + wn * 4 + nf;
-                if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+                for (int nf = 0; nf < 4; ++nf) {
+                    const int nb = cur.nt * 16 + wn * 4 + nf;
+                    if (nb >= nblk) continue;
+                    store_out<FIRST>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+                }
             }
         }
+        cur = nxt;
     }
 }
 
