@@ -333,6 +333,12 @@ hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hip
 }
 
 // chunk size (tokens per routing block) and wavefronts per block, from the shape alone
+#ifndef ROUTE_BIG_T
+#define ROUTE_BIG_T 8192   // from this many tokens on: 64 tokens per block
+#endif
+#ifndef ROUTE_BIG_NW
+#define ROUTE_BIG_NW 4     // wavefronts per block (contraction slices) of the 64-token variant
+#endif
 struct RouteCfg { int tok, nw, nf; };
 static RouteCfg route_cfg(const moe_shape& s) {
     RouteCfg c{16, 4, 1};
@@ -341,6 +347,7 @@ static RouteCfg route_cfg(const moe_shape& s) {
     if (route_is_split(s)) { c.tok = 16; c.nw = 8; return c; }   // the split path works in chunks of 16 tokens
     if (s.T <= 64) { c.tok = 16; c.nw = 16; c.nf = c.nf > 4 ? 4 : c.nf; }   // few blocks: split the contraction 16 ways
                                                                             // (128 registers per lane: 4 fragments at a time)
+    else if (s.T >= ROUTE_BIG_T && s.E <= 256) { c.tok = 64; c.nw = ROUTE_BIG_NW; }   // 4 token fragments per gate-weight fragment
     else if (s.T >= 4096 && s.E <= 256) { c.tok = 32; c.nw = 8; }
     else { c.tok = 16; c.nw = 8; }
     return c;
@@ -481,6 +488,7 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
         return launch_route_small(s, x, w_gate, bias, idx, gate, margin, chunk_hist, gate_part_ws, st);
     const RouteCfg c = route_cfg(s);
     if (c.nw == 16) return launch_route_nf<1, 16>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    if (c.tok == 64) return launch_route_nf<4, ROUTE_BIG_NW>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
     if (c.tok == 32) return launch_route_nf<2, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
     return launch_route_nf<1, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
 }
