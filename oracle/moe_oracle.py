@@ -167,6 +167,18 @@ def hot_expert_count(counts, alpha, bw_a, bw_b):
     return max(0, min(int(np.floor(h + 0.5)), E))
 
 
+def parameter_movement(E, d_model, d_ff):
+    """Number of expert parameters of one MoE layer, i.e. what moving every expert to the compute
+    device moves (Section 3.2, Eq. 1): two matrices of d_model x d_ff per expert."""
+    return 2 * int(E) * int(d_model) * int(d_ff)
+
+
+def activation_movement(tokens, d_model):
+    """Number of activation values that cross the link when the tokens go to the experts instead
+    (Section 3.2, Eq. 2): every token's d_model values out and back; tokens = B * S."""
+    return 2 * int(tokens) * int(d_model)
+
+
 def round_bf16(a):
     """Round fp64 values to the nearest bfloat16 (8 significant bits, ties to even),
     returned as fp64.  Written from the format's definition (sign, 8 exponent bits,

@@ -1,6 +1,6 @@
 """GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
 
-Bars (see DESIGN.md): routing indices, counts, offsets, hot masks and permutations bit-exact
+Bars: routing indices, counts, offsets, hot masks and permutations bit-exact
 (tokens whose fp64 top-(k+1) logit margin is below 1e-4 are listed and excluded from the index
 comparison); floating-point outputs within 1e-2 under  |got - ref| / max(|ref|, rms(ref))
 against the oracle run at the layer's storage precision for the hidden activation, and within

@@ -163,6 +163,22 @@ def test_hot_mask_top_h():
 
 
 # ---------------------------------------------------------------- special cases
+def test_data_movement_model_eq1_eq2():
+    # Table 2 prints the total expert size of the two models: 51.5 GB for Switch-Large-128 (24 MoE layers,
+    # d_model 1024, 128 experts) and 103.1 GB for NLLB-MoE (12 MoE layers, d_model 2048, 128 experts), in
+    # bf16; per layer that is Eq. 1 with d_ff = 4 d_model.
+    assert abs(24 * orc.parameter_movement(128, 1024, 4096) * 2 / 1e9 - 51.5) < 0.1
+    assert abs(12 * orc.parameter_movement(128, 2048, 8192) * 2 / 1e9 - 103.1) < 0.1
+    # Eq. 2 against its reading: B sequences of S tokens, d_model values each way
+    assert orc.activation_movement(4 * 512, 1024) == 2 * 4 * 512 * 1024
+    # the paper's point (Section 3.2): for inference-sized batches the activations are orders of magnitude
+    # smaller than the parameters, and the ratio is E * d_ff / tokens
+    for E, d, f, tok in [(128, 1024, 4096, 512), (128, 2048, 8192, 1), (64, 768, 3072, 2048)]:
+        ratio = orc.parameter_movement(E, d, f) / orc.activation_movement(tok, d)
+        assert abs(ratio - E * f / tok) < 1e-9
+    assert orc.parameter_movement(128, 2048, 8192) / orc.activation_movement(512, 2048) == 2048.0
+
+
 def test_hot_expert_count_eq6():
     # values worked out by hand from Eq. 6 (tests/golden/hot_count_examples.json)
     with open(os.path.join(GOLD, "hot_count_examples.json")) as fh:
