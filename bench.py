@@ -102,6 +102,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0,
                     help="weight copies rotated through the timing loop (0 = enough for 2 GB between reuses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--measure-fetch", action="store_true",
+                    help="also time moe_fetch_experts (activated experts' W1 from pinned host memory) and log the rate")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -247,6 +249,25 @@ def main() -> int:
              "useful_GBps": layer_bytes / (ms_step * 1e-3) / 1e9,
              "useful_bytes": layer_bytes, "flops": layer_flops,
              "experts_run": n_active, "assignments_run": A_run, **{k_: round(v, 2) for k_, v in br.items()}}
+
+    # ---- optional: parameter movement on demand over the host link (Section 3.2), logged only ----------
+    if args.measure_fetch and cfg.dtype == "bf16":
+        fetch_mask = torch.from_numpy(ran.astype(np.uint8))
+        host_w1 = L.w1.cpu().pin_memory()
+        dst = torch.empty_like(L.w1)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for rep in range(2):                               # first pass warms the pinned pages up
+            ev0.record()
+            moe.moe_fetch_experts(L.shape, 1, host_w1, fetch_mask, dst)
+            ev1.record()
+            torch.cuda.synchronize()
+        fb = int(ran.sum()) * d * f * es
+        fms = ev0.elapsed_time(ev1)
+        log(f"[bench] moe_fetch_experts: {int(ran.sum())} activated experts' W1, {fb / 1e6:.1f} MB from pinned host "
+            f"memory in {fms:.3f} ms = {fb / fms / 1e6:.1f} GB/s (Eq. 1 for the whole layer: "
+            f"{moe.moe_parameter_movement_bytes(L.shape) / 1e6:.1f} MB, Eq. 2: "
+            f"{moe.moe_activation_movement_bytes(L.shape) / 1e6:.2f} MB)")
+        del host_w1, dst
 
     # ---- CPU oracle on a bounded sample of the same workload -------------------------------------
     cpu = None

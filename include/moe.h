@@ -108,6 +108,26 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Data-movement model of Section 3.2, in bytes of the shape's storage dtype (host arithmetic, no GPU):
+ *   parameter movement  (Eq. 1) = 2 * E * d_model * d_ff  values: all experts' weights to the compute device;
+ *   activation movement (Eq. 2) = 2 * T * d_model        values: the tokens to the experts and back.
+ * 0 on a bad shape.
+ */
+size_t moe_parameter_movement_bytes(const moe_shape* shape);
+size_t moe_activation_movement_bytes(const moe_shape* shape);
+
+/*
+ * Parameter movement on demand (Section 3.2, Section 4.1: only activated experts are brought in): copies the
+ * packed weights (`which` = 1: W1, 2: W2) of the experts with fetch_mask[e] != 0 from a HOST buffer holding all
+ * E experts' packed weights (layout of moe_pack_weights; pinned memory for an asynchronous copy) to the same
+ * offsets of a DEVICE buffer of the same size, one copy per expert on `stream`; other experts' device memory
+ * is left as it is.  fetch_mask is a HOST array [E] -- the caller has brought counts or a hot mask over, that
+ * being the one host round trip the scheme needs.  Returns after enqueueing; MOE_ERR_HIP if a copy fails.
+ */
+moe_status moe_fetch_experts(const moe_shape* shape, int32_t which, const void* src_host,
+                             const uint8_t* fetch_mask_host, void* dst_device, void* stream);
+
+/*
  * Hot-set size of the load-balancing rule (Section 3.3, Eq. 3-6) and the hot mask it implies.
  * The hot workflow is fed at bandwidth bw_a, the cold one at bw_b (any common unit); both are
  * bound by moving expert parameters, so equal runtimes put bw_a / (bw_a + bw_b) of the activated

@@ -22,6 +22,7 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 
 EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
+           "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_fetch_experts",
            "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]
 
 
@@ -67,6 +68,12 @@ def load() -> ctypes.CDLL:
     lib.moe_route.restype = ctypes.c_int
     lib.moe_route.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.moe_permute.restype = ctypes.c_int
+    lib.moe_parameter_movement_bytes.argtypes = [sp]
+    lib.moe_parameter_movement_bytes.restype = sz
+    lib.moe_activation_movement_bytes.argtypes = [sp]
+    lib.moe_activation_movement_bytes.restype = sz
+    lib.moe_fetch_experts.argtypes = [sp, i32, vp, vp, vp, vp]
+    lib.moe_fetch_experts.restype = ctypes.c_int
     lib.moe_select_hot.argtypes = [sp, vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, vp, vp, vp]
     lib.moe_select_hot.restype = ctypes.c_int
     lib.moe_permute.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -149,6 +156,21 @@ def moe_route(shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, off
     _check(load().moe_route(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(topk_idx),
                             _ptr(topk_w), _ptr(margin), _ptr(counts), _ptr(offsets), int(H), _ptr(hot_mask),
                             _ptr(ws), _nbytes(ws), _stream(stream)), "moe_route")
+
+
+def moe_parameter_movement_bytes(shape) -> int:
+    return int(load().moe_parameter_movement_bytes(ctypes.byref(shape)))
+
+
+def moe_activation_movement_bytes(shape) -> int:
+    return int(load().moe_activation_movement_bytes(ctypes.byref(shape)))
+
+
+def moe_fetch_experts(shape, which, src_host, fetch_mask_host, dst_device, stream=None) -> None:
+    """src_host, fetch_mask_host: CPU tensors (pinned for an asynchronous copy); dst_device: CUDA tensor."""
+    _check(load().moe_fetch_experts(ctypes.byref(shape), int(which), ctypes.c_void_p(src_host.data_ptr()),
+                                    ctypes.c_void_p(fetch_mask_host.data_ptr()), _ptr(dst_device), _stream(stream)),
+           "moe_fetch_experts")
 
 
 def moe_select_hot(shape, counts, alpha, bw_a, bw_b, H_out, hot_mask, stream=None) -> None:

@@ -89,6 +89,33 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, 
                                  static_cast<hipStream_t>(stream)));
 }
 
+size_t moe_parameter_movement_bytes(const moe_shape* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return static_cast<size_t>(2) * shape->E * shape->d_model * shape->d_ff * elem_size(shape->dtype);
+}
+
+size_t moe_activation_movement_bytes(const moe_shape* shape) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return static_cast<size_t>(2) * shape->T * shape->d_model * elem_size(shape->dtype);
+}
+
+moe_status moe_fetch_experts(const moe_shape* shape, int32_t which, const void* src_host,
+                             const uint8_t* fetch_mask_host, void* dst_device, void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((which != 1 && which != 2) || src_host == nullptr || fetch_mask_host == nullptr || dst_device == nullptr)
+        return MOE_ERR_INVALID_ARG;
+    const size_t per_expert = static_cast<size_t>(shape->d_model) * shape->d_ff * elem_size(shape->dtype);
+    for (int e = 0; e < shape->E; ++e) {
+        if (fetch_mask_host[e] == 0) continue;
+        const hipError_t err = hipMemcpyAsync(static_cast<char*>(dst_device) + e * per_expert,
+                                              static_cast<const char*>(src_host) + e * per_expert, per_expert,
+                                              hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+        if (err != hipSuccess) return MOE_ERR_HIP;
+    }
+    return MOE_OK;
+}
+
 moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double alpha, double bw_a, double bw_b,
                           int32_t* H_out, uint8_t* hot_mask, void* stream) {
     moe_status st = check_shape(shape);

@@ -20,7 +20,7 @@ def declared_functions():
 def test_header_and_binding_agree():
     names = declared_functions()
     assert sorted(moe.EXPORTS) == names
-    for n in ["moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
+    for n in ["moe_route", "moe_select_hot", "moe_fetch_experts", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
         assert n in names and callable(getattr(moe, n))
 
 
@@ -100,6 +100,21 @@ def test_bad_pointers_and_workspace_are_rejected():
     assert lib.moe_select_hot(ctypes.byref(s), FAKE, -1.0, 1.0, 1.0, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
     assert lib.moe_select_hot(ctypes.byref(s), FAKE, 1.0, 0.0, 1.0, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
     assert lib.moe_select_hot(ctypes.byref(s), FAKE, 1.0, 1.0, float("nan"), FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+
+
+def test_data_movement_calculators():
+    # host arithmetic of the library against the oracle's Eq. 1-2 (Section 3.2); bytes = values * storage size
+    from oracle import moe_oracle as orc
+    for kw, es in [(dict(), 2), (dict(dtype="f32"), 4), (dict(T=2048, d_model=768, d_ff=3072, E=64, k=1), 2)]:
+        s = shape(**kw)
+        assert moe.moe_parameter_movement_bytes(s) == orc.parameter_movement(s.E, s.d_model, s.d_ff) * es
+        assert moe.moe_activation_movement_bytes(s) == orc.activation_movement(s.T, s.d_model) * es
+    assert moe.moe_parameter_movement_bytes(shape(k=9)) == 0
+    lib = moe.load()
+    s = shape()
+    assert lib.moe_fetch_experts(ctypes.byref(s), 3, FAKE, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_fetch_experts(ctypes.byref(s), 1, None, FAKE, FAKE, None) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_fetch_experts(ctypes.byref(s), 1, FAKE, None, FAKE, None) == moe.MOE_ERR_INVALID_ARG
 
 
 def test_binding_raises_on_error():

@@ -404,6 +404,46 @@ def test_select_hot(gpu_lib, name):
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------------------ on-demand expert fetch
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["many_experts", "ragged_bf16"])
+def test_fetch_experts(gpu_lib, name):
+    """Parameter movement on demand (Section 3.2): with only the activated experts' packed weights brought
+    over from pinned host memory, the layer computes the same bits as with all weights resident, and the
+    other experts' device memory is not touched."""
+    cfg = CFG(name)
+    say(f"[case] moe_fetch_experts {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    L.forward()
+    torch.cuda.synchronize()
+    want = L.out.clone()
+    active = (np.asarray(r["counts"]) > 0).astype(np.uint8)
+    assert 0 < active.sum() < cfg.E or name != "many_experts"       # the case has idle experts
+    host = [w.cpu().pin_memory() for w in (L.w1, L.w2)]
+    fill = torch.full_like(L.w1, float("nan"))
+    dev = [fill.clone(), fill.clone()]
+    side = torch.cuda.Stream()
+    mask_host = torch.from_numpy(active)
+    with torch.cuda.stream(side):
+        for which in (1, 2):
+            gpu_lib.moe_fetch_experts(L.shape, which, host[which - 1], mask_host, dev[which - 1],
+                                      stream=side.cuda_stream)
+    side.synchronize()
+    for which in (0, 1):
+        got, ref = dev[which].view(torch.int16), (L.w1, L.w2)[which].view(torch.int16)
+        on = torch.from_numpy(active.astype(bool)).cuda()
+        assert torch.equal(got[on], ref[on])
+        assert torch.equal(got[~on], fill.view(torch.int16)[~on])
+    gpu_lib.moe_layer_forward(L.shape, L.x, L.w_gate, L.b_gate, dev[0], dev[1], None, -1, L.out, ws=L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.out.view(torch.int16), want.view(torch.int16))
+    s = L.shape
+    say(f"[movement] {name}: parameters {gpu_lib.moe_parameter_movement_bytes(s)} B (Eq. 1), activations "
+        f"{gpu_lib.moe_activation_movement_bytes(s)} B (Eq. 2), fetched "
+        f"{int(active.sum())} of {cfg.E} experts")
+
+
 # ------------------------------------------------------------------------------ degenerate inputs
 def test_no_tokens_and_empty_mask(gpu_lib):
     from paper_2405_18832_amd.device_layer import DeviceLayer
