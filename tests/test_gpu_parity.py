@@ -444,6 +444,40 @@ def test_fetch_experts(gpu_lib, name):
         f"{int(active.sum())} of {cfg.E} experts")
 
 
+# ------------------------------------------------------------------------------ HIP graph capture
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["ragged_bf16", "switch_large_skew_matched"])
+def test_layer_forward_in_a_graph(gpu_lib, name):
+    """The whole layer allocates nothing, never synchronises and clears its counters with kernels, so it can
+    be captured into a HIP graph.  Every replay is checked against an eager run on the same inputs, with
+    eager work (new activations, an eager forward, synchronisations) between the replays."""
+    say(f"[case] graph capture {name}")
+    L = device_layer(gpu_lib, name)
+    x0 = L.x.clone()
+    L.forward()                                   # eager first: one-time kernel attribute calls happen here
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        L.forward()
+    torch.cuda.synchronize()
+    try:
+        for rep in range(4):
+            # new inputs: the token rows in another order (routing and every expert's row set change)
+            perm = torch.randperm(x0.shape[0], generator=torch.Generator().manual_seed(rep)).cuda()
+            L.x.copy_(x0[perm])
+            L.forward()
+            torch.cuda.synchronize()
+            want = L.out.clone()
+            L.out.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(L.out.view(torch.int16), want.view(torch.int16)), f"replay {rep}"
+    finally:
+        L.x.copy_(x0)
+        torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------------------ degenerate inputs
 def test_no_tokens_and_empty_mask(gpu_lib):
     from paper_2405_18832_amd.device_layer import DeviceLayer
