@@ -199,16 +199,20 @@ def gelu(z):
     return 0.5 * z * (1.0 + erf(z / np.sqrt(2.0)))
 
 
-def expert_ffn(X_e, W1_e, W2_e, h_dtype=None, activation="relu"):
-    """Y = act(X W1^T) W2^T for one expert (Section 2.1: two linear layers with an
+def expert_ffn(X_e, W1_e, W2_e, h_dtype=None, activation="relu", b1_e=None, b2_e=None):
+    """Y = act(X W1^T + b1) W2^T + b2 for one expert (Section 2.1: two linear layers with an
     activation in between; Section 3.4: a gemm with a trailing ReLU or GeLU, then a gemm).
-    W1_e [f, d], W2_e [d, f]; no biases.  activation = "relu" (default) or "gelu".
+    W1_e [f, d], W2_e [d, f]; activation = "relu" (default) or "gelu".  The paper's experts are the
+    two weight matrices; b1_e [f] and b2_e [d] (default: none) are the biases that linear layers of
+    released checkpoints of the NLLB family carry, added the way a linear layer adds them.
 
     h_dtype = None keeps the hidden activation in fp64 (the exact definition).
     h_dtype = "bf16" rounds it once to bfloat16 before the second product, which is
     what a bfloat16 inference run (Section 4.1) stores between the two linear layers;
     all sums stay in fp64."""
     h = np.asarray(X_e, F64) @ np.asarray(W1_e, F64).T
+    if b1_e is not None:
+        h = h + np.asarray(b1_e, F64)[None, :]
     if activation == "relu":
         h = np.maximum(h, 0.0)
     elif activation == "gelu":
@@ -219,7 +223,10 @@ def expert_ffn(X_e, W1_e, W2_e, h_dtype=None, activation="relu"):
         h = round_bf16(h)
     elif h_dtype not in (None, "f32", "f64"):
         raise ValueError(h_dtype)
-    return h @ np.asarray(W2_e, F64).T
+    y = h @ np.asarray(W2_e, F64).T
+    if b2_e is not None:
+        y = y + np.asarray(b2_e, F64)[None, :]
+    return y
 
 
 def permute_tokens(x, perm, k):
@@ -256,8 +263,9 @@ def route(x, w_gate, b_gate, k, renormalize):
 
 def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
                   return_intermediates=False, h_dtype=None, activation="relu"):
-    """Whole MoE FFN layer.  `expert(e)` returns (W1_e, W2_e); it is called only for
-    experts that received tokens and are not masked out.  With a mask, only the
+    """Whole MoE FFN layer.  `expert(e)` returns (W1_e, W2_e) or, for experts with biases,
+    (W1_e, W2_e, b1_e, b2_e); it is called only for experts that received tokens and are not
+    masked out.  With a mask, only the
     masked-in experts' share of the output is produced (Section 3.3: hot experts
     on one device, the rest elsewhere; gates are fixed before the split)."""
     x = np.asarray(x, F64)
@@ -271,8 +279,8 @@ def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         if hi == lo or (mask is not None and not mask[e]):
             continue
-        W1_e, W2_e = expert(e)
-        y_perm[lo:hi] = expert_ffn(x_perm[lo:hi], W1_e, W2_e, h_dtype, activation)
+        we = expert(e)
+        y_perm[lo:hi] = expert_ffn(x_perm[lo:hi], we[0], we[1], h_dtype, activation, *we[2:4])
     out = combine(y_perm, inv, idx, g, mask)
     if return_intermediates:
         r.update(perm=perm, inv_perm=inv, x_perm=x_perm, y_perm=y_perm, out=out)
@@ -280,7 +288,8 @@ def layer_forward(x, w_gate, b_gate, expert, k, renormalize, mask=None,
     return out
 
 
-def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None, activation="relu"):
+def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None, activation="relu",
+                     b1=None, b2=None):
     """Dense definition: run every expert on every token, then keep each token's
     top-k experts, weight and sum.  Tiny inputs only."""
     x = np.asarray(x, F64)
@@ -288,7 +297,8 @@ def layer_bruteforce(x, w_gate, b_gate, W1, W2, k, renormalize, mask=None, activ
     E = w_gate.shape[0]
     Yall = np.empty((T, E, d), F64)
     for e in range(E):
-        Yall[:, e, :] = expert_ffn(x, W1[e], W2[e], activation=activation)
+        Yall[:, e, :] = expert_ffn(x, W1[e], W2[e], activation=activation,
+                                   b1_e=None if b1 is None else b1[e], b2_e=None if b2 is None else b2[e])
     L = gate_logits(x, w_gate, b_gate)
     p = softmax_rows(L)
     idx = topk_experts(L, k)

@@ -269,6 +269,32 @@ def test_gelu_variant():
         orc.expert_ffn(x, W1[0], W2[0], activation="silu")
 
 
+def test_expert_biases():
+    x, wg, b, W1, W2 = tiny(T=9, E=4, k=2, bias=True)
+    rng = np.random.default_rng(5)
+    b1, b2 = rng.standard_normal((4, W1.shape[1])), rng.standard_normal((4, W2.shape[1]))
+    # one expert against a library's linear layers
+    xt = torch.from_numpy(x)
+    lin = torch.nn.functional.linear
+    ref = lin(torch.relu(lin(xt, torch.from_numpy(W1[2]), torch.from_numpy(b1[2]))), torch.from_numpy(W2[2]),
+              torch.from_numpy(b2[2])).numpy()
+    assert np.allclose(orc.expert_ffn(x, W1[2], W2[2], b1_e=b1[2], b2_e=b2[2]), ref, rtol=1e-12, atol=1e-12)
+    # zero biases change nothing; the output bias is a plain shift; the hidden bias is not (ReLU in between)
+    y0 = orc.expert_ffn(x, W1[2], W2[2])
+    assert np.array_equal(orc.expert_ffn(x, W1[2], W2[2], b1_e=np.zeros_like(b1[2]), b2_e=np.zeros_like(b2[2])), y0)
+    assert np.allclose(orc.expert_ffn(x, W1[2], W2[2], b2_e=b2[2]) - y0, b2[2][None, :], atol=1e-12)
+    assert not np.allclose(orc.expert_ffn(x, W1[2], W2[2], b1_e=b1[2]) - y0, (b1[2] @ W2[2].T)[None, :], atol=1e-6)
+    # in the layer: brute force over all experts, and with renormalised gates the output biases of the chosen
+    # experts enter with weights that sum to one
+    out = orc.layer_forward(x, wg, b, lambda e: (W1[e], W2[e], b1[e], b2[e]), 2, True)
+    bf = orc.layer_bruteforce(x, wg, b, W1, W2, 2, True, b1=b1, b2=b2)
+    assert np.allclose(out, bf, rtol=1e-12, atol=1e-12)
+    same = np.tile(b2[:1], (4, 1))
+    out_s = orc.layer_forward(x, wg, b, lambda e: (W1[e], W2[e], None, same[e]), 2, True)
+    out_0 = orc.layer_forward(x, wg, b, lambda e: (W1[e], W2[e]), 2, True)
+    assert np.allclose(out_s - out_0, same[:1], atol=1e-12)
+
+
 def test_expert_relabelling_and_token_permutation():
     x, wg, b, W1, W2 = tiny(T=11, E=6, k=2, bias=True, seed=5)
     base = run(x, wg, b, W1, W2, 2, True)
