@@ -169,6 +169,17 @@ moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void
                           float* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moe_expert_ffn with expert biases, as the linear layers of some released MoE checkpoints carry them (the
+ * paper's experts are the two weight matrices, Section 2.1; this is the optional variant):
+ *   y_perm[rows of e] = act(x_perm[rows] . W1_e^T + b1_e) . W2_e^T + b2_e
+ * b1 [E, d_ff] and b2 [E, d_model]: fp32, device, row e = expert e; either may be NULL (no bias).  Everything
+ * else as moe_expert_ffn, which is this call with both NULL.
+ */
+moe_status moe_expert_ffn_biased(const moe_shape* shape, const void* x_perm, const void* w1, const float* b1,
+                                 const void* w2, const float* b2, const int32_t* offsets, const uint8_t* mask,
+                                 float* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Combine (Section 2.1: outputs are combined and re-organised into the original token order):
  *   out[t] = sum over j < k with mask[topk_idx[t,j]] != 0 of topk_w[t,j] * y_perm[inv_perm[t*k+j]]
  * accumulated in fp32, rounded once to dtype.  Masked-out rows of y_perm are not read.
@@ -204,6 +215,13 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
                              const uint8_t* mask, int32_t H, void* out,
                              int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* perm,
                              uint8_t* hot_mask_out, void* ws, size_t ws_bytes, void* stream);
+
+/* moe_layer_forward with expert biases (see moe_expert_ffn_biased); moe_layer_forward is this call with b1 = b2 = NULL. */
+moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const void* w_gate,
+                                    const float* gate_bias, const void* w1, const float* b1, const void* w2,
+                                    const float* b2, const uint8_t* mask, int32_t H, void* out, int32_t* topk_idx,
+                                    float* topk_w, int32_t* counts, int32_t* perm, uint8_t* hot_mask_out, void* ws,
+                                    size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

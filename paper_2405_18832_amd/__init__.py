@@ -23,7 +23,8 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
            "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_fetch_experts",
-           "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]
+           "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_biased", "moe_combine",
+           "moe_layer_forward", "moe_layer_forward_biased"]
 
 
 class MoEError(RuntimeError):
@@ -80,6 +81,10 @@ def load() -> ctypes.CDLL:
     lib.moe_expert_ffn.restype = ctypes.c_int
     lib.moe_expert_ffn.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_combine.restype = ctypes.c_int
+    lib.moe_expert_ffn_biased.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_expert_ffn_biased.restype = ctypes.c_int
+    lib.moe_layer_forward_biased.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_layer_forward_biased.restype = ctypes.c_int
     lib.moe_combine.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_layer_forward.restype = ctypes.c_int
     lib.moe_layer_forward.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -188,6 +193,21 @@ def moe_expert_ffn(shape, x_perm, w1, w2, offsets, mask, y_perm, ws, stream=None
     _check(load().moe_expert_ffn(ctypes.byref(shape), _ptr(x_perm), _ptr(w1), _ptr(w2), _ptr(offsets),
                                  _ptr(mask), _ptr(y_perm), _ptr(ws), _nbytes(ws), _stream(stream)),
            "moe_expert_ffn")
+
+
+def moe_expert_ffn_biased(shape, x_perm, w1, b1, w2, b2, offsets, mask, y_perm, ws, stream=None) -> None:
+    _check(load().moe_expert_ffn_biased(ctypes.byref(shape), _ptr(x_perm), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2),
+                                        _ptr(offsets), _ptr(mask), _ptr(y_perm), _ptr(ws), _nbytes(ws),
+                                        _stream(stream)), "moe_expert_ffn_biased")
+
+
+def moe_layer_forward_biased(shape, x, w_gate, gate_bias, w1, b1, w2, b2, mask, H, out, topk_idx=None, topk_w=None,
+                             counts=None, perm=None, hot_mask_out=None, ws=None, stream=None) -> None:
+    _check(load().moe_layer_forward_biased(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(w1),
+                                           _ptr(b1), _ptr(w2), _ptr(b2), _ptr(mask), int(H), _ptr(out),
+                                           _ptr(topk_idx), _ptr(topk_w), _ptr(counts), _ptr(perm),
+                                           _ptr(hot_mask_out), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "moe_layer_forward_biased")
 
 
 def moe_combine(shape, y_perm, inv_perm, topk_idx, topk_w, mask, out, stream=None) -> None:

@@ -145,6 +145,12 @@ moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* top
 moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void* w1, const void* w2,
                           const int32_t* offsets, const uint8_t* mask, float* y_perm, void* ws, size_t ws_bytes,
                           void* stream) {
+    return moe_expert_ffn_biased(shape, x_perm, w1, nullptr, w2, nullptr, offsets, mask, y_perm, ws, ws_bytes, stream);
+}
+
+moe_status moe_expert_ffn_biased(const moe_shape* shape, const void* x_perm, const void* w1, const float* b1,
+                                 const void* w2, const float* b2, const int32_t* offsets, const uint8_t* mask,
+                                 float* y_perm, void* ws, size_t ws_bytes, void* stream) {
     moe_status st = check_shape(shape);
     if (st != MOE_OK) return st;
     if (shape->T == 0) return MOE_OK;
@@ -153,7 +159,7 @@ moe_status moe_expert_ffn(const moe_shape* shape, const void* x_perm, const void
     st = check_ws(shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
     const WsLayout L = ws_layout(*shape);
-    return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, offsets, mask, y_perm, at<void>(ws, L.h),
+    return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, b1, b2, offsets, mask, y_perm, at<void>(ws, L.h),
                                       at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big), at<int32_t>(ws, L.ntiles),
                                       at<float>(ws, L.partials), at<void>(ws, L.x_kmajor), static_cast<hipStream_t>(stream)));
 }
@@ -173,6 +179,15 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
                              const void* w1, const void* w2, const uint8_t* mask, int32_t H, void* out,
                              int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* perm,
                              uint8_t* hot_mask_out, void* ws, size_t ws_bytes, void* stream) {
+    return moe_layer_forward_biased(shape, x, w_gate, gate_bias, w1, nullptr, w2, nullptr, mask, H, out, topk_idx,
+                                    topk_w, counts, perm, hot_mask_out, ws, ws_bytes, stream);
+}
+
+moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const void* w_gate,
+                                    const float* gate_bias, const void* w1, const float* b1, const void* w2,
+                                    const float* b2, const uint8_t* mask, int32_t H, void* out, int32_t* topk_idx,
+                                    float* topk_w, int32_t* counts, int32_t* perm, uint8_t* hot_mask_out, void* ws,
+                                    size_t ws_bytes, void* stream) {
     moe_status st = check_shape(shape);
     if (st != MOE_OK) return st;
     if (shape->T > 0 && (x == nullptr || w_gate == nullptr || w1 == nullptr || w2 == nullptr || out == nullptr))
@@ -220,10 +235,10 @@ moe_status moe_layer_forward(const moe_shape* shape, const void* x, const void* 
         void* xk = at<void>(ws, L.x_kmajor);
         e = launch_gather_kmajor(*shape, x, tokmap, xk, hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
-        e = launch_expert_products(*shape, xk, nullptr, true, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
+        e = launch_expert_products(*shape, xk, nullptr, true, w1, w2, b1, b2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
                                    hs);
     } else {
-        e = launch_expert_products(*shape, x, tokmap, false, w1, w2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
+        e = launch_expert_products(*shape, x, tokmap, false, w1, w2, b1, b2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
                                    hs);
     }
     if (e != hipSuccess) return MOE_ERR_HIP;

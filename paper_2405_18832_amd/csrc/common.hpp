@@ -252,19 +252,20 @@ hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* o
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
 int ffn_tile_rows(const moe_shape& s);
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
-                                  const void* w1, const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
-                                  hipStream_t st);
+                                  const void* w1, const void* w2, const float* b1, const float* b2, float* y_perm,
+                                  void* h_ws, const TileLists& lists, hipStream_t st);
 bool layer_gathers_kmajor(const moe_shape& s);
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
                                float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
-                               hipStream_t st);
+                               const float* bias, hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,
                           int32_t* hist_ws, hipStream_t st);
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
+                             const float* b1, const float* b2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm,
                              void* h_ws, Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
                              void* x_kmajor_ws, hipStream_t st);

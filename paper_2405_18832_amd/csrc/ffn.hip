@@ -122,7 +122,8 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
                                             const int K, const int kb0, const int kb1, f32x4* red,
-                                            const int rows_total, const bool act_kmajor) {
+                                            const int rows_total, const bool act_kmajor,
+                                            const float* __restrict__ bias) {
     constexpr int PF = StreamPF<TFC>::value;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -214,6 +215,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
         }
     }
     if (active && ks == 0) {
+        const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) {
             const int lr = tf * 16 + r;
@@ -222,7 +224,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = ng * 4 + nf;
                 if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
             }
         }
     }
@@ -241,7 +243,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
                                                 const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                                 const Tile tl, const int ng, const bool active, const int N,
                                                 const int K, const int rows_total, const bool act_kmajor,
-                                                unsigned char* tok_lds) {
+                                                const float* __restrict__ bias, unsigned char* tok_lds) {
     constexpr int PF = MOE_PF_LDS;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -321,6 +323,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
         for (int p = 0; p < PF; ++p)
             if (kb + p < kblk) fma(p, kb + p);
 
+        const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) {
             const int lr = tf * 16 + r;
@@ -329,7 +332,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
             for (int nf = 0; nf < 4; ++nf) {
                 const int nb = ng * 4 + nf;
                 if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
             }
         }
     }
@@ -345,11 +348,12 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
-                                                         int rows_total, int act_kmajor, int rows_in_lds) {
+                                                         int rows_total, int act_kmajor, int rows_in_lds,
+                                                         const float* __restrict__ bias) {
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total);
+    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total, bias);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -384,23 +388,23 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         if (KSPLIT == 1 && rows_in_lds) {
             const bool km = act_kmajor != 0;
             if (TFMAX >= 4 && tfc == 4)
-                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
             else if (TFMAX >= 4 && tfc == 3)
-                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
             else if (TFMAX >= 2 && tfc == 2)
-                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
             else
-                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, tok_lds);
+                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
             continue;
         }
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
+            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
+            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
+            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0);
+            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
     }
 }
 
@@ -415,7 +419,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
                                                       float* __restrict__ outp,
                                                       const Tile* __restrict__ tiles,
                                                       const int32_t* __restrict__ ntiles_p, int N, int K,
-                                                      int activation) {
+                                                      int activation, const float* __restrict__ bias) {
     const int nchunks = (N + 255) / 256;
     const int nbu = ntiles_p[0] * nchunks;
     for (int bu = blockIdx.x; bu < nbu; bu += gridDim.x) {
@@ -428,6 +432,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
             const float* ar = act + static_cast<size_t>(src) * K;
             float s = 0.f;
             for (int c = 0; c < K; ++c) s = fmaf(ar[c], wr[c], s);
+            if (bias) s += bias[static_cast<size_t>(tl.expert) * N + n];
             outp[static_cast<size_t>(tl.row0 + i) * N + n] = FIRST ? activate(s, activation) : s;
         }
     }
@@ -452,7 +457,7 @@ template <int TFMAX, int KSPLIT, int FIRST>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
                                 const Tile* big_tiles, const float* partials, int rows_total, bool act_kmajor,
-                                hipStream_t st) {
+                                const float* bias, hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
     static int per_cu = 0;
     if (per_cu == 0) {
@@ -481,7 +486,7 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), lds, st, act, rowmap, wpk, outp, tiles,
                        ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total,
-                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0);
+                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0, bias);
     return hipGetLastError();
 }
 
@@ -489,16 +494,16 @@ template <int TFMAX, int FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
-                                  bool act_kmajor, hipStream_t st) {
+                                  bool act_kmajor, const float* bias, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
         return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                              big_tiles, partials, rows_total, act_kmajor, st);
+                                              big_tiles, partials, rows_total, act_kmajor, bias, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, st);
+                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, bias, st);
     return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, st);
+                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, bias, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -557,8 +562,8 @@ bool layer_gathers_kmajor(const moe_shape& s) {
 }
 
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
-                                  const void* w1, const void* w2, float* y_perm, void* h_ws, const TileLists& lists,
-                                  hipStream_t st) {
+                                  const void* w1, const void* w2, const float* b1, const float* b2, float* y_perm,
+                                  void* h_ws, const TileLists& lists, hipStream_t st) {
     const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
     const int tile_rows = lists.small_rows;
     const Tile* tiles = lists.small_tiles;
@@ -576,13 +581,13 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
         if ((err = mark(1, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(static_cast<unsigned>(g1 < cap ? g1 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(act), rowmap, static_cast<const float*>(w1),
-                           static_cast<float*>(h_ws), tiles, ntiles, f, d, s.activation);
+                           static_cast<float*>(h_ws), tiles, ntiles, f, d, s.activation, b1);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
         if ((err = mark(2, st)) != hipSuccess || (err = mark(3, st)) != hipSuccess) return err;
         hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(static_cast<unsigned>(g2 < cap ? g2 : cap)), dim3(256), 0, st,
                            static_cast<const float*>(h_ws), static_cast<const int32_t*>(nullptr),
-                           static_cast<const float*>(w2), y_perm, tiles, ntiles, d, f, s.activation);
+                           static_cast<const float*>(w2), y_perm, tiles, ntiles, d, f, s.activation, b2);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
         return mark(4, st);
@@ -599,36 +604,37 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
     // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
     if (big) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, s.activation, st);
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, s.activation, b1, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
     const bool gelu = s.activation == MOE_ACT_GELU;
     switch (ffn_tfmax(s) * 2 + (gelu ? 1 : 0)) {
-        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
-        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
-        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
-        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
-        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
-        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, st); break;
+        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
     if (big) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, s.activation, st);
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, s.activation, b2, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
-        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
-        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, st); break;
+        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
+        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
+        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);
 }
 
 hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void* w1, const void* w2,
+                             const float* b1, const float* b2,
                              const int32_t* offsets, const uint8_t* mask, float* y_perm, void* h_ws,
                              Tile* tiles_ws, Tile* tiles_big_ws, int32_t* ntiles_ws, float* partials_ws,
                              void* x_kmajor_ws, hipStream_t st) {
@@ -639,9 +645,9 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
     if (layer_gathers_kmajor(s)) {      // large layer: re-lay the permuted rows k-step-major first
         err = launch_gather_kmajor(s, x_perm, nullptr, x_kmajor_ws, st);
         if (err != hipSuccess) return err;
-        return launch_expert_products(s, x_kmajor_ws, nullptr, true, w1, w2, y_perm, h_ws, lists, st);
+        return launch_expert_products(s, x_kmajor_ws, nullptr, true, w1, w2, b1, b2, y_perm, h_ws, lists, st);
     }
-    return launch_expert_products(s, x_perm, nullptr, false, w1, w2, y_perm, h_ws, lists, st);
+    return launch_expert_products(s, x_perm, nullptr, false, w1, w2, b1, b2, y_perm, h_ws, lists, st);
 }
 
 }  // namespace moe

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ ntiles_p,
                                                        int32_t* __restrict__ part_counter,
                                                        float* __restrict__ partials, int N, int K,
-                                                       int rows_total, int act_kmajor) {
+                                                       int rows_total, int act_kmajor,
+                                                       const float* __restrict__ bias) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // between units, when no stage is in use, the first word of the ring passes the next part's number on
     int* next_part = reinterpret_cast<int*>(smem);
@@ -276,6 +277,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                     *reinterpret_cast<f32x4*>(mine + (wm * 128 + tf * 16 + r) * kTN + (wn * 4 + nf) * 16 + g * 4) =
                         acc[nf][tf];
         } else {
+            const float* be = bias ? bias + static_cast<size_t>(cur.tl.expert) * N : nullptr;
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf) {
                 const int lr = wm * 128 + tf * 16 + r;
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                 for (int nf = 0; nf < 4; ++nf) {
                     const int nb = cur.nt * 16 + wn * 4 + nf;
                     if (nb >= nblk) continue;
-                    store_out<FIRST>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, acc[nf][tf]);
+                    store_out<FIRST>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
                 }
             }
         }
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 template <int FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                               const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
-                              int K, int rows_total, bool act_kmajor, hipStream_t st) {
+                              int K, int rows_total, bool act_kmajor, const float* bias, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
     constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
     static bool configured = false;
@@ -309,7 +311,7 @@ static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const 
     // only known on the device, and few units are cut along K over blocks that would otherwise idle.
     const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0);
+                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0, bias);
     return hipGetLastError();
 }
 
@@ -318,15 +320,15 @@ int tile_product_grid() { return device_cu_count(); }
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
                                float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
-                               hipStream_t st) {
+                               const float* bias, hipStream_t st) {
     if (!first)
         return launch_tile<0>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                              act_kmajor, st);
+                              act_kmajor, bias, st);
     if (activation == MOE_ACT_GELU)
         return launch_tile<kFirstGelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                                       act_kmajor, st);
+                                       act_kmajor, bias, st);
     return launch_tile<kFirstRelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                                   act_kmajor, st);
+                                   act_kmajor, bias, st);
 }
 
 }  // namespace moe

@@ -57,9 +57,12 @@ __device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, i
 
 // 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST != 0 (first product; the value
 // names the activation, kFirstRelu or kFirstGelu): activation, bf16, into the k-step-major h of `rows_total`
-// rows; FIRST == 0 (second product): fp32 into row-major y of N columns.
+// rows; FIRST == 0 (second product): fp32 into row-major y of N columns.  `bias`: the expert's N bias values
+// (fp32) or NULL, added before the activation / the store.
 template <int FIRST>
-__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const f32x4 v) {
+__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const float* bias,
+                                          f32x4 v) {
+    if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n);
     if (FIRST) {
         const f32x4 z = activate4<FIRST == kFirstGelu ? MOE_ACT_GELU : MOE_ACT_RELU>(v);
         uint2 pk;
@@ -76,7 +79,8 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
 template <int FIRST>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
-                                                   int N, int kblk, int G, int rows_total) {
+                                                   int N, int kblk, int G, int rows_total,
+                                                   const float* __restrict__ bias) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
@@ -94,7 +98,8 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
         f32x4 sum = *reinterpret_cast<const f32x4*>(base);
         for (int p = 1; p < s.split; ++p)
             sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
-        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, sum);
+        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total,
+                         bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr, sum);
     }
 }
 #endif

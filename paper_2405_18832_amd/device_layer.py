@@ -12,7 +12,8 @@ from typing import Callable, Iterable, Optional
 import numpy as np
 import torch
 
-from . import (make_shape, moe_combine, moe_expert_ffn, moe_layer_forward, moe_pack_weights,
+from . import (make_shape, moe_combine, moe_expert_ffn, moe_expert_ffn_biased, moe_layer_forward,
+               moe_layer_forward_biased, moe_pack_weights,
                moe_permute, moe_route, moe_workspace_bytes)
 
 
@@ -28,12 +29,13 @@ def to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
 class DeviceLayer:
     def __init__(self, cfg, x: np.ndarray, w_gate: np.ndarray, b_gate: Optional[np.ndarray],
                  expert: Callable[[int], tuple], experts: Optional[Iterable[int]] = None,
-                 device: str = "cuda:0", workers: int = 8):
+                 device: str = "cuda:0", workers: int = 8, biases: Optional[tuple] = None):
         """cfg needs T, d_model, d_ff, E, k, dtype ("f32"|"bf16"), renormalize.
         `expert(e)` returns (W1_e [d_ff, d_model], W2_e [d_model, d_ff]).  If `experts` is
         given, only those experts get their real weights; the others are filled with
         device-generated normal noise of the same scale (used when only a known subset can
-        receive tokens and generating all weights on the host would take minutes)."""
+        receive tokens and generating all weights on the host would take minutes).
+        `biases` = (b1 [E, d_ff], b2 [E, d_model]) float32 arrays for experts with biases."""
         self.cfg = cfg
         self.device = torch.device(device)
         act = {"relu": 0, "gelu": 1}[getattr(cfg, "activation", "relu")]
@@ -61,6 +63,10 @@ class DeviceLayer:
                 self.w2[e] = (torch.randn((d * f,), device=dev, generator=gen) / f ** 0.5).to(td)
         self.upload_experts(expert, want, workers)
         self.weight_copies = [(self.w1, self.w2)]
+        self.b1 = self.b2 = None
+        if biases is not None:
+            self.b1 = torch.from_numpy(np.ascontiguousarray(biases[0], dtype=np.float32)).to(dev)
+            self.b2 = torch.from_numpy(np.ascontiguousarray(biases[1], dtype=np.float32)).to(dev)
 
         self.ws = torch.empty(max(256, moe_workspace_bytes(self.shape)), dtype=torch.uint8, device=dev)
         i32, f32 = torch.int32, torch.float32
@@ -111,8 +117,12 @@ class DeviceLayer:
 
     def expert_ffn(self, mask=None, x_perm=None, offsets=None, copy: int = 0):
         w1, w2 = self.weight_copies[copy % len(self.weight_copies)]
-        moe_expert_ffn(self.shape, self.x_perm if x_perm is None else x_perm, w1, w2,
-                       self.offsets if offsets is None else offsets, mask, self.y_perm, self.ws)
+        xp = self.x_perm if x_perm is None else x_perm
+        off = self.offsets if offsets is None else offsets
+        if self.b1 is None and self.b2 is None:
+            moe_expert_ffn(self.shape, xp, w1, w2, off, mask, self.y_perm, self.ws)
+        else:
+            moe_expert_ffn_biased(self.shape, xp, w1, self.b1, w2, self.b2, off, mask, self.y_perm, self.ws)
 
     def combine(self, mask=None, y_perm=None, inv_perm=None, topk_idx=None, topk_w=None):
         moe_combine(self.shape, self.y_perm if y_perm is None else y_perm,
@@ -122,13 +132,13 @@ class DeviceLayer:
 
     def forward(self, mask=None, H: int = -1, debug: bool = False, copy: int = 0):
         w1, w2 = self.weight_copies[copy % len(self.weight_copies)]
-        if debug:
-            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, w1, w2, mask, H,
-                              self.out, self.topk_idx, self.topk_w, self.counts, self.perm, self.hot_mask,
-                              self.ws)
+        dbg = (self.topk_idx, self.topk_w, self.counts, self.perm, self.hot_mask) if debug else (None,) * 5
+        if self.b1 is None and self.b2 is None:
+            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, w1, w2, mask, H, self.out, *dbg,
+                              ws=self.ws)
         else:
-            moe_layer_forward(self.shape, self.x, self.w_gate, self.b_gate, w1, w2, mask, H,
-                              self.out, ws=self.ws)
+            moe_layer_forward_biased(self.shape, self.x, self.w_gate, self.b_gate, w1, self.b1, w2, self.b2, mask, H,
+                                     self.out, *dbg, ws=self.ws)
         return self.out
 
     def out_numpy(self) -> np.ndarray:

@@ -20,7 +20,7 @@ def declared_functions():
 def test_header_and_binding_agree():
     names = declared_functions()
     assert sorted(moe.EXPORTS) == names
-    for n in ["moe_route", "moe_select_hot", "moe_fetch_experts", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
+    for n in ["moe_route", "moe_select_hot", "moe_fetch_experts", "moe_expert_ffn_biased", "moe_layer_forward_biased", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"]:
         assert n in names and callable(getattr(moe, n))
 
 

@@ -39,7 +39,10 @@ def oracle_route(name):
 
 @functools.lru_cache(maxsize=72)
 def expert_cached(name, e):
-    return wl.make_expert(CFG(name), e)
+    """(W1_e, W2_e), or (W1_e, W2_e, b1_e, b2_e) for configs whose experts carry biases."""
+    cfg = CFG(name)
+    w = wl.make_expert(cfg, e)
+    return w + wl.make_expert_bias(cfg, e) if cfg.expert_bias else w
 
 
 EXTRA = {
@@ -69,6 +72,16 @@ EXTRA = {
                                 renormalize=False, seed=22, zipf_s=1.0, gate_std=0.3, activation="gelu"),
     "gelu_wide": wl.MoEConfig("gelu_wide", T=96, d_model=256, d_ff=3072, E=6, k=2, dtype="bf16",
                               renormalize=True, seed=23, gate_std=0.3, activation="gelu"),
+    # experts with biases: fp32 kernel, streaming kernel (rows in LDS / split contraction), tiled kernel
+    # incl. its K-cut last round, together with GeLU
+    "bias_f32": wl.MoEConfig("bias_f32", T=64, d_model=64, d_ff=256, E=8, k=2, dtype="f32", renormalize=True,
+                             seed=31, expert_bias=True),
+    "bias_ragged": wl.MoEConfig("bias_ragged", T=333, d_model=96, d_ff=160, E=11, k=2, dtype="bf16",
+                                renormalize=False, seed=32, zipf_s=1.0, gate_std=0.3, expert_bias=True),
+    "bias_wide_gelu": wl.MoEConfig("bias_wide_gelu", T=96, d_model=256, d_ff=3072, E=6, k=2, dtype="bf16",
+                                   renormalize=True, seed=33, gate_std=0.3, activation="gelu", expert_bias=True),
+    "bias_all_to_one": wl.MoEConfig("bias_all_to_one", T=700, d_model=2048, d_ff=512, E=8, k=1, dtype="bf16",
+                                    renormalize=False, seed=34, zipf_s=40.0, expert_bias=True),
     "gelu_all_to_one": wl.MoEConfig("gelu_all_to_one", T=700, d_model=2048, d_ff=512, E=8, k=1, dtype="bf16",
                                     renormalize=False, seed=24, zipf_s=40.0, activation="gelu"),
 }
@@ -81,7 +94,8 @@ def CFG(name):
 
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
-         "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one"]
+         "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
+         "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"]
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128"]
 LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4"]
 
@@ -106,8 +120,12 @@ def device_layer(gpu_lib, name):
         experts = [e for e in range(cfg.E) if r["counts"][e] > 0]
     say(f"[upload] {name}: T={cfg.T} d={cfg.d_model} f={cfg.d_ff} E={cfg.E} k={cfg.k} "
         f"real experts={'all' if experts is None else len(experts)}")
-    L = DeviceLayer(cfg, r["x"], r["wg"], r["b"], lambda e: expert_cached(name, e), experts=experts,
-                    workers=8)
+    biases = None
+    if cfg.expert_bias:
+        bs = [wl.make_expert_bias(cfg, e) for e in range(cfg.E)]
+        biases = (np.stack([b[0] for b in bs]), np.stack([b[1] for b in bs]))
+    L = DeviceLayer(cfg, r["x"], r["wg"], r["b"], lambda e: expert_cached(name, e)[:2], experts=experts,
+                    workers=8, biases=biases)
     _layers[name] = L
     return L
 
@@ -210,9 +228,9 @@ def oracle_ffn_rows(r, cfg, rows_by_expert):
     hd = "bf16" if cfg.dtype == "bf16" else None
     experts = [e for e in range(cfg.E) if r["offsets"][e + 1] > r["offsets"][e]]
     for e, rows in zip(experts, rows_by_expert):
-        W1, W2 = expert_cached(cfg.name, e)
-        ref_s.append(orc.expert_ffn(x_perm[rows], W1, W2, hd, cfg.activation))
-        ref_x.append(orc.expert_ffn(x_perm[rows], W1, W2, None, cfg.activation))
+        we = expert_cached(cfg.name, e)
+        ref_s.append(orc.expert_ffn(x_perm[rows], we[0], we[1], hd, cfg.activation, *we[2:4]))
+        ref_x.append(orc.expert_ffn(x_perm[rows], we[0], we[1], None, cfg.activation, *we[2:4]))
         pos.append(rows)
     return np.concatenate(pos), np.concatenate(ref_s), np.concatenate(ref_x)
 
@@ -289,8 +307,8 @@ def oracle_expert_outputs(r, cfg, tokens, h_dtype):
         for j in range(cfg.k):
             need.setdefault(int(r["idx"][t, j]), []).append((ti, t, j))
     for e, lst in sorted(need.items()):
-        W1, W2 = expert_cached(cfg.name, e)
-        y = orc.expert_ffn(r["x"][[t for _, t, _ in lst]], W1, W2, h_dtype, cfg.activation)
+        we = expert_cached(cfg.name, e)
+        y = orc.expert_ffn(r["x"][[t for _, t, _ in lst]], we[0], we[1], h_dtype, cfg.activation, *we[2:4])
         for (ti, t, j), yrow in zip(lst, y):
             ys[ti, j] = yrow
     return ys

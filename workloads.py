@@ -81,6 +81,7 @@ class MoEConfig:
     H: Optional[int] = None          # hot mask = top-H experts by token count
     gate_std: float = 0.02
     activation: str = "relu"        # trailing activation of the first linear layer: "relu" | "gelu"
+    expert_bias: bool = False       # experts carry biases b1 [d_ff], b2 [d_model] (fp32, N(0, 0.25^2))
 
     @property
     def A(self) -> int:
@@ -167,6 +168,16 @@ def make_expert(cfg: MoEConfig, e: int):
     w2 = _rng(cfg.seed, _TAG_W2, e).standard_normal((cfg.d_model, cfg.d_ff), dtype=np.float32)
     w2 *= np.float32(1.0 / np.sqrt(cfg.d_ff))
     return round_to_storage(w1, cfg.dtype), round_to_storage(w2, cfg.dtype)
+
+
+_TAG_B1, _TAG_B2 = 101, 102
+
+
+def make_expert_bias(cfg: MoEConfig, e: int):
+    """(b1_e [d_ff], b2_e [d_model]) as float32, for configs with expert_bias."""
+    b1 = _rng(cfg.seed, _TAG_B1, e).standard_normal(cfg.d_ff, dtype=np.float32) * np.float32(0.25)
+    b2 = _rng(cfg.seed, _TAG_B2, e).standard_normal(cfg.d_model, dtype=np.float32) * np.float32(0.25)
+    return b1, b2
 
 
 @dataclass
