@@ -61,13 +61,13 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "a99f2695e6c0f682", "ffn_tile.hip": "5dd78e6189ff2015",
-                   "tile_schedule.hpp": "5b63a029925c33ac", "common.hpp": "5657580f24370dd2"}
+TRAFFIC_SOURCES = {"ffn.hip": "541e990ed2bf3ea7", "ffn_tile.hip": "a697a5158a9492b5",
+                   "tile_schedule.hpp": "fe137f7300bc71c8", "common.hpp": "800d8276aa1ee582"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316696248, ("switch_base", "stream_w2"): 322259562,
-    ("nllb_decode", "stream_w1"): 1644036009, ("nllb_decode", "stream_w2"): 1645980642,
-    ("nllb_prefill_skew", "stream_w1"): 1158888353, ("nllb_prefill_skew", "stream_w2"): 1152859066,
-    ("nllb_prefill_skew", "tile_w1"): 2505343314, ("nllb_prefill_skew", "tile_w2"): 2214736534,
+    ("switch_base", "stream_w1"): 316287408, ("switch_base", "stream_w2"): 321724401,
+    ("nllb_decode", "stream_w1"): 1643665483, ("nllb_decode", "stream_w2"): 1645603802,
+    ("nllb_prefill_skew", "stream_w1"): 1158669071, ("nllb_prefill_skew", "stream_w2"): 1152616948,
+    ("nllb_prefill_skew", "tile_w1"): 2503513257, ("nllb_prefill_skew", "tile_w2"): 2209077780,
 }
 
 
