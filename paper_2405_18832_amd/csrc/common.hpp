@@ -197,7 +197,10 @@ struct WsLayout {
 // contraction into kGateSplit slices (partial logits in the workspace).  Measured: a gain up to 64 tokens
 // (one block per 16 tokens leaves reading the gate weights to a few CUs), none at 2048 tokens.
 constexpr int kGateSplit = 8;
-constexpr int kSplitRouteTokens = 64;
+#ifndef MOE_SPLIT_ROUTE_TOKENS
+#define MOE_SPLIT_ROUTE_TOKENS 64
+#endif
+constexpr int kSplitRouteTokens = MOE_SPLIT_ROUTE_TOKENS;
 inline bool route_is_split(const moe_shape& s) { return s.dtype == MOE_BF16 && s.T <= kSplitRouteTokens; }
 constexpr int kPermChunk = 256;   // assignments per counting-sort chunk (one wavefront)
 
