@@ -333,6 +333,12 @@ hipError_t launch_mask_out(const uint8_t* mask_or_null, uint8_t* dst, int E, hip
 }
 
 // chunk size (tokens per routing block) and wavefronts per block, from the shape alone
+#ifndef ROUTE_MID_NW
+#define ROUTE_MID_NW 4     // wavefronts per block of the 16-token variant (measured: 4 < 2 < 8 < 1 < 16 in time)
+#endif
+#ifndef ROUTE_T4K_NW
+#define ROUTE_T4K_NW 4      // wavefronts per block of the 32-token variant
+#endif
 #ifndef ROUTE_BIG_T
 #define ROUTE_BIG_T 8192   // from this many tokens on: 64 tokens per block
 #endif
@@ -348,8 +354,8 @@ static RouteCfg route_cfg(const moe_shape& s) {
     if (s.T <= 64) { c.tok = 16; c.nw = 16; c.nf = c.nf > 4 ? 4 : c.nf; }   // few blocks: split the contraction 16 ways
                                                                             // (128 registers per lane: 4 fragments at a time)
     else if (s.T >= ROUTE_BIG_T && s.E <= 256) { c.tok = 64; c.nw = ROUTE_BIG_NW; }   // 4 token fragments per gate-weight fragment
-    else if (s.T >= 4096 && s.E <= 256) { c.tok = 32; c.nw = 8; }
-    else { c.tok = 16; c.nw = 8; }
+    else if (s.T >= 4096 && s.E <= 256) { c.tok = 32; c.nw = ROUTE_T4K_NW; }
+    else { c.tok = 16; c.nw = ROUTE_MID_NW; }
     return c;
 }
 
@@ -489,8 +495,8 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
     const RouteCfg c = route_cfg(s);
     if (c.nw == 16) return launch_route_nf<1, 16>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
     if (c.tok == 64) return launch_route_nf<4, ROUTE_BIG_NW>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
-    if (c.tok == 32) return launch_route_nf<2, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
-    return launch_route_nf<1, 8>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    if (c.tok == 32) return launch_route_nf<2, ROUTE_T4K_NW>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
+    return launch_route_nf<1, ROUTE_MID_NW>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
 }
 
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
