@@ -61,13 +61,13 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "541e990ed2bf3ea7", "ffn_tile.hip": "a697a5158a9492b5",
-                   "tile_schedule.hpp": "fe137f7300bc71c8", "common.hpp": "800d8276aa1ee582"}
+TRAFFIC_SOURCES = {"ffn.hip": "e6c7e22ab25c3780", "ffn_tile.hip": "a697a5158a9492b5",
+                   "tile_schedule.hpp": "dc1e57eac5a84857", "common.hpp": "9b240c5d89192dea"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316287408, ("switch_base", "stream_w2"): 321724401,
-    ("nllb_decode", "stream_w1"): 1643665483, ("nllb_decode", "stream_w2"): 1645603802,
-    ("nllb_prefill_skew", "stream_w1"): 1158669071, ("nllb_prefill_skew", "stream_w2"): 1152616948,
-    ("nllb_prefill_skew", "tile_w1"): 2503513257, ("nllb_prefill_skew", "tile_w2"): 2209077780,
+    ("switch_base", "stream_w1"): 321829707, ("switch_base", "stream_w2"): 321695745,
+    ("nllb_decode", "stream_w1"): 1644094470, ("nllb_decode", "stream_w2"): 1645611771,
+    ("nllb_prefill_skew", "stream_w1"): 1164126682, ("nllb_prefill_skew", "stream_w2"): 1152682864,
+    ("nllb_prefill_skew", "tile_w1"): 2522962368, ("nllb_prefill_skew", "tile_w2"): 2208274900,
 }
 
 

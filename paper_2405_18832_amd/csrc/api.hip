@@ -219,16 +219,21 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
         e = launch_route_fused(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, at<float>(ws, L.gate_part), hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
+    // few assignments: the finalize block also places them (one launch less)
+    const bool fused_place = shape->T > 0 && scan_can_place(*shape);
+    const PlaceArgs place{idx, perm, inv, tokmap, shape->T * shape->k, shape->k, tok * shape->k};
     e = launch_scan_finalize(hist, nchunks, shape->E, cnt, offsets, derive ? H : -1, derive ? own_mask : nullptr,
-                             mask, &lists, hs);
+                             mask, &lists, fused_place ? &place : nullptr, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (hot_mask_out != nullptr) {
         e = launch_mask_out(used, hot_mask_out, shape->E, hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
     if (shape->T == 0) return MOE_OK;
-    e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
-    if (e != hipSuccess) return MOE_ERR_HIP;
+    if (!fused_place) {
+        e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
+        if (e != hipSuccess) return MOE_ERR_HIP;
+    }
     if (layer_gathers_kmajor(*shape)) {
         // layers large enough for the tiled kernel: one pass gathers the token rows into the k-step-major
         // layout that lets both kernels fetch operand rows as full cache lines

@@ -124,6 +124,43 @@ struct TileLists {
 };
 
 #ifdef __HIPCC__
+// Places one chunk of consecutive flat assignment ids (counting sort, last step): called by one whole
+// wavefront.  `next` (LDS, E ints, private to the wavefront) holds each expert's first free slot for this
+// chunk and is advanced.  The wavefront walks its chunk 64 flat ids at a time; lanes that hold the same
+// expert find each other with one ballot per bit of the expert id, take consecutive slots in lane order,
+// and the last of them advances the expert's slot.  Writes (each may be NULL) perm[pos] = a,
+// inv_perm[a] = pos, tokmap[pos] = a / k.
+__device__ __forceinline__ void place_chunk(const int32_t* __restrict__ idx, int32_t* next,
+                                            int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                            int32_t* __restrict__ tokmap, int A, int E, int k, int ebits, int chunk,
+                                            int c) {
+    const int lane = threadIdx.x & 63;
+    const int base = c * chunk;
+    for (int i0 = 0; i0 < chunk; i0 += 64) {
+        const int a = base + i0 + lane;
+        const bool live = (i0 + lane < chunk) && a < A;
+        const int e = live ? min(max(idx[a], 0), E - 1) : 0;   // clamped: a bad index must not fault
+        uint64_t same = __ballot(live);
+        for (int b = 0; b < ebits; ++b) {
+            const uint64_t has = __ballot(live && ((e >> b) & 1));
+            same &= ((e >> b) & 1) ? has : ~has;
+        }
+        const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        const int rank = __popcll(same & below);
+        int pos = 0;
+        if (live) pos = next[e] + rank;
+        __builtin_amdgcn_wave_barrier();
+        const bool last = live && ((same >> lane) >> 1) == 0;   // no higher lane with this expert
+        if (last) next[e] = pos + 1;
+        __builtin_amdgcn_wave_barrier();
+        if (live && pos >= 0 && pos < A) {   // offsets that do not belong to idx must not fault
+            if (perm) perm[pos] = a;
+            if (inv_perm) inv_perm[a] = pos;
+            if (tokmap) tokmap[pos] = a / k;
+        }
+    }
+}
+
 // Inclusive prefix sum over the 1024 threads of a block (thread e contributes v): shuffles inside each
 // wavefront, one LDS round for the 16 wavefront totals.  `tmp` is an LDS array of >= 16 ints; two barriers.
 __device__ __forceinline__ int block_scan_1024(int v, int32_t* tmp) {
@@ -248,8 +285,18 @@ hipError_t launch_select_hot(int E, const int32_t* counts, double alpha, double 
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* gate_part_ws,
                               hipStream_t st);
+// what the finalize kernel needs to place the assignments itself (small layers: one launch less)
+struct PlaceArgs {
+    const int32_t* idx;    // nullptr: do not place
+    int32_t* perm;
+    int32_t* inv_perm;
+    int32_t* tokmap;
+    int A, k, chunk;
+};
+bool scan_can_place(const moe_shape& s);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
-                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st);
+                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists,
+                                const PlaceArgs* place, hipStream_t st);
 TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32_t* ntiles_ws, float* partials_ws);
 hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);

@@ -115,6 +115,34 @@ template <> struct StreamPF<2> { static constexpr int value = MOE_PF_TF2; };
 template <> struct StreamPF<3> { static constexpr int value = MOE_PF_TF3; };
 template <> struct StreamPF<4> { static constexpr int value = MOE_PF_TF4; };
 
+// Output of one column group (4 n-blocks) x TFC row fragments of a tile, by one whole wavefront.
+template <int TFC, int FIRST>
+__device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile tl, const int ng, const int nblk,
+                                            const int N, const int rows_total, const float* __restrict__ be,
+                                            const f32x4 (&acc)[4][TFC]) {
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int tf = 0; tf < TFC; ++tf) {
+        const int lr = tf * 16 + r;
+        const bool ok = lr < tl.rows;
+        if constexpr (FIRST != 0) {
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const int nb = ng * 4 + 2 * m;             // N / 16 is even: the pair exists or not as a whole
+                if (nb >= nblk) continue;                  // wave-uniform
+                store_h_pair<FIRST, true>(outp, tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
+            }
+        } else {
+#pragma unroll
+            for (int nf = 0; nf < 4; ++nf) {
+                const int nb = ng * 4 + nf;
+                if (ok && nb < nblk)
+                    store_out<0, true>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+            }
+        }
+    }
+}
+
 // One wavefront's share of one unit: 4 n-blocks x TFC token fragments over k-steps [kb0, kb1).
 template <int TFC, int TFMAX, int KSPLIT, int FIRST>
 __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
@@ -216,17 +244,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     }
     if (active && ks == 0) {
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-#pragma unroll
-        for (int tf = 0; tf < TFC; ++tf) {
-            const int lr = tf * 16 + r;
-            if (lr >= tl.rows) continue;
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf) {
-                const int nb = ng * 4 + nf;
-                if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
-            }
-        }
+        store_group<TFC, FIRST>(outp, tl, ng, nblk, N, rows_total, be, acc);
     }
     if (KSPLIT > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // `red` may be reused
 }
@@ -324,17 +342,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
             if (kb + p < kblk) fma(p, kb + p);
 
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-#pragma unroll
-        for (int tf = 0; tf < TFC; ++tf) {
-            const int lr = tf * 16 + r;
-            if (lr >= tl.rows) continue;
-#pragma unroll
-            for (int nf = 0; nf < 4; ++nf) {
-                const int nb = ng * 4 + nf;
-                if (nb >= nblk) continue;
-                store_out<FIRST>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
-            }
-        }
+        store_group<TFC, FIRST>(outp, tl, ng, nblk, N, rows_total, be, acc);
     }
 }
 

@@ -281,12 +281,22 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 #pragma unroll
             for (int tf = 0; tf < 8; ++tf) {
                 const int lr = wm * 128 + tf * 16 + r;
-                if (lr >= cur.tl.rows) continue;
+                const bool ok = lr < cur.tl.rows;
+                if constexpr (FIRST != 0) {
 #pragma unroll
-                for (int nf = 0; nf < 4; ++nf) {
-                    const int nb = cur.nt * 16 + wn * 4 + nf;
-                    if (nb >= nblk) continue;
-                    store_out<FIRST>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                    for (int m = 0; m < 2; ++m) {
+                        const int nb = cur.nt * 16 + wn * 4 + 2 * m;   // N / 16 is even: a pair exists as a whole
+                        if (nb >= nblk) continue;                       // wave-uniform
+                        store_h_pair<FIRST, false>(outp, cur.tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf],
+                                                   acc[2 * m + 1][tf]);
+                    }
+                } else {
+#pragma unroll
+                    for (int nf = 0; nf < 4; ++nf) {
+                        const int nb = cur.nt * 16 + wn * 4 + nf;
+                        if (ok && nb < nblk)
+                            store_out<0>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                    }
                 }
             }
         }

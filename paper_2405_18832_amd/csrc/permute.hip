@@ -53,30 +53,7 @@ __global__ __launch_bounds__(256) void perm_place_kernel(const int32_t* __restri
     int32_t* next = next_all[wave];
     for (int e = lane; e < E; e += 64) next[e] = offsets[e] + chunk_base[static_cast<size_t>(e) * nchunks + c];
     __builtin_amdgcn_wave_barrier();
-    const int base = c * chunk;
-    for (int i0 = 0; i0 < chunk; i0 += 64) {
-        const int a = base + i0 + lane;
-        const bool live = (i0 + lane < chunk) && a < A;
-        const int e = live ? min(max(idx[a], 0), E - 1) : 0;   // clamped: a bad index must not fault
-        uint64_t same = __ballot(live);
-        for (int b = 0; b < ebits; ++b) {
-            const uint64_t has = __ballot(live && ((e >> b) & 1));
-            same &= ((e >> b) & 1) ? has : ~has;
-        }
-        const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-        const int rank = __popcll(same & below);
-        int pos = 0;
-        if (live) pos = next[e] + rank;
-        __builtin_amdgcn_wave_barrier();
-        const bool last = live && ((same >> lane) >> 1) == 0;   // no higher lane with this expert
-        if (last) next[e] = pos + 1;
-        __builtin_amdgcn_wave_barrier();
-        if (live && pos >= 0 && pos < A) {   // offsets that do not belong to idx must not fault
-            if (perm) perm[pos] = a;
-            if (inv_perm) inv_perm[a] = pos;
-            if (tokmap) tokmap[pos] = a / k;
-        }
-    }
+    place_chunk(idx, next, perm, inv_perm, tokmap, A, E, k, ebits, chunk, c);
 }
 
 // gather: x_perm[p] = x[perm[p] / k]; one wavefront per row, 16 bytes (or 4) per lane and step
@@ -153,7 +130,7 @@ hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                        nchunks);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    err = launch_scan_finalize(hist_ws, nchunks, E, nullptr, nullptr, -1, nullptr, nullptr, nullptr, st);
+    err = launch_scan_finalize(hist_ws, nchunks, E, nullptr, nullptr, -1, nullptr, nullptr, nullptr, nullptr, st);
     if (err != hipSuccess) return err;
     err = launch_place(s, idx, offsets, hist_ws, perm, inv_perm, nullptr, kPermChunk, st);
     if (err != hipSuccess) return err;

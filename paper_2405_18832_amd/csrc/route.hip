@@ -227,14 +227,19 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
 //           cut into row tiles: one list for small experts, one for large ones).
 // Any output pointer may be NULL.
 // ---------------------------------------------------------------------------
+constexpr int kScanPlaceMaxE = 256;     // largest E and ...
+constexpr long kScanPlaceMaxA = 512;    // ... most assignments for which the finalize block also places
+
 __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
                                                              int E, int32_t* __restrict__ counts,
                                                              int32_t* __restrict__ offsets, int H,
                                                              uint8_t* __restrict__ hot_mask,
                                                              const uint8_t* __restrict__ mask_in,
-                                                             const TileLists lists, const int want_tiles) {
+                                                             const TileLists lists, const int want_tiles,
+                                                             const PlaceArgs place) {
     __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
+    __shared__ int32_t place_next[16][kScanPlaceMaxE];   // per wavefront: next free slot of every expert
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // phase 1: wavefront w owns experts w, w+16, ...; it walks them 8 at a time so that the 8 rows'
     // loads are in flight together (chunk_hist is [E][nchunks]: a row is contiguous)
@@ -286,8 +291,25 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     } else if (mask_in != nullptr && e < E) {
         on = mask_in[e] != 0;
     }
-    if (!want_tiles) return;           // uniform: a kernel argument
-    emit_tiles(e, row0, on ? mine : 0, lists, scan);
+    if (want_tiles) emit_tiles(e, row0, on ? mine : 0, lists, scan);     // uniform: a kernel argument
+    if (place.idx == nullptr) return;                                    // uniform
+    // Small layers: this block also places the assignments (the last step of the counting sort), wavefront
+    // w taking chunks w, w + 16, ...: one launch less on a path that is a chain of short kernels.  The slot
+    // bases written to chunk_hist in phase 1 are read back by the same block after a barrier.
+    __syncthreads();
+    if (e < E) cnt[e] = row0;                                            // cnt now holds the offsets
+    __threadfence_block();
+    __syncthreads();
+    int ebits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    int32_t* next = place_next[wave];
+    for (int c = wave; c < nchunks; c += 16) {
+        for (int x = lane; x < E; x += 64) next[x] = cnt[x] + chunk_hist[static_cast<size_t>(x) * nchunks + c];
+        __builtin_amdgcn_wave_barrier();
+        place_chunk(place.idx, next, place.perm, place.inv_perm, place.tokmap, place.A, E, place.k, ebits,
+                    place.chunk, c);
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // Hot-set size from the counts (Section 3.3, Eq. 6) and the top-H mask.  One block, thread e owns
@@ -499,11 +521,19 @@ hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_g
     return launch_route_nf<1, ROUTE_MID_NW>(c.nf, s, x, w_gate, bias, idx, gate, margin, chunk_hist, st);
 }
 
+// the finalize block places the assignments itself when there are few of them and the per-wavefront slot
+// tables fit into LDS
+bool scan_can_place(const moe_shape& s) {
+    return s.E <= kScanPlaceMaxE && static_cast<long>(s.T) * s.k <= kScanPlaceMaxA;
+}
+
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
-                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists, hipStream_t st) {
+                                uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists,
+                                const PlaceArgs* place, hipStream_t st) {
     const TileLists none{nullptr, nullptr, nullptr, nullptr, 16, 0};
+    const PlaceArgs no_place{nullptr, nullptr, nullptr, nullptr, 0, 1, 1};
     hipLaunchKernelGGL(scan_finalize_kernel, dim3(1), dim3(1024), 0, st, chunk_hist, nchunks, E, counts, offsets, H,
-                       hot_mask, mask_in, lists ? *lists : none, lists ? 1 : 0);
+                       hot_mask, mask_in, lists ? *lists : none, lists ? 1 : 0, place ? *place : no_place);
     return hipGetLastError();
 }
 
@@ -518,7 +548,7 @@ hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, c
         hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, gate_part_ws, st);
         if (err != hipSuccess) return err;
     }
-    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, st);
+    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, nullptr, st);
 }
 
 }  // namespace moe

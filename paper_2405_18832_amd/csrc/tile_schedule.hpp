@@ -58,8 +58,12 @@ __device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, i
 // 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST != 0 (first product; the value
 // names the activation, kFirstRelu or kFirstGelu): activation, bf16, into the k-step-major h of `rows_total`
 // rows; FIRST == 0 (second product): fp32 into row-major y of N columns.  `bias`: the expert's N bias values
-// (fp32) or NULL, added before the activation / the store.
-template <int FIRST>
+// (fp32) or NULL, added before the activation / the store.  STREAMED: the store carries the non-temporal
+// hint, so the rows go to memory while the kernel runs instead of staying behind as dirty L2 lines that the
+// next kernel's weight stream has to push out (the streaming kernel's stores; measured on the Switch-base
+// preset: following product 65 -> 62 us; no effect on the fp32 rows of the second product, which are stored
+// plainly).  The tiled kernel's rows are re-read from L2 and are stored plainly.
+template <int FIRST, bool STREAMED = false>
 __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const float* bias,
                                           f32x4 v) {
     if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n);
@@ -68,9 +72,49 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
         uint2 pk;
         pk.x = pack_bf16x2(z[0], z[1]);
         pk.y = pack_bf16x2(z[2], z[3]);
-        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total)) = pk;
+        uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total));
+        if (STREAMED) {
+            __builtin_nontemporal_store(pk.x, q);      // merged into one 8-byte store
+            __builtin_nontemporal_store(pk.y, q + 1);
+        } else {
+            *reinterpret_cast<uint2*>(q) = pk;
+        }
     } else {
         *reinterpret_cast<f32x4*>(static_cast<float*>(outp) + static_cast<size_t>(row) * N + n) = v;
+    }
+}
+
+// First-product output of two adjacent 16-column blocks (columns n0 ... n0 + 31: one k-step block of h) for
+// the 16 rows of an accumulator pair.  Called by a whole wavefront (no divergence around it): lane (r, g),
+// r = lane % 16 the row, g = lane / 16, holds columns n0 + 4g ... + 3 in v0 and n0 + 16 + 4g ... + 3 in v1.
+// After activation and rounding, one v_permlane16_swap per packed register trades the odd 16-lane rows of the
+// first block with the even rows of the second, which leaves every lane with 8 consecutive columns of its
+// row: the wavefront's store is one contiguous KiB of h (16 rows x 64 bytes) instead of two stores of
+// 32-byte pieces.  `row_ok`: the lane's row exists (the others take part in the exchange only).
+template <int FIRST, bool STREAMED>
+__device__ __forceinline__ void store_h_pair(void* outp, int row, bool row_ok, int n0, int rows_total,
+                                             const float* bias, f32x4 v0, f32x4 v1) {
+    static_assert(FIRST != 0, "first product only");
+    const int g = (threadIdx.x & 63) >> 4;
+    if (bias != nullptr) {
+        v0 += *reinterpret_cast<const f32x4*>(bias + n0 + g * 4);
+        v1 += *reinterpret_cast<const f32x4*>(bias + n0 + 16 + g * 4);
+    }
+    constexpr int ACT = FIRST == kFirstGelu ? MOE_ACT_GELU : MOE_ACT_RELU;
+    const f32x4 z0 = activate4<ACT>(v0), z1 = activate4<ACT>(v1);
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16x2(z0[0], z0[1]), pack_bf16x2(z1[0], z1[1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16x2(z0[2], z0[3]), pack_bf16x2(z1[2], z1[3]), false, false);
+    // even g: columns 4g ... 4g + 7 of the first block; odd g: columns 4(g-1) ... + 7 of the second
+    const int n = n0 + (g & 1) * 16 + (g & 2) * 4;
+    if (!row_ok) return;
+    uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total));
+    if (STREAMED) {
+        __builtin_nontemporal_store(lo[0], q);             // merged into one 16-byte store
+        __builtin_nontemporal_store(hi[0], q + 1);
+        __builtin_nontemporal_store(lo[1], q + 2);
+        __builtin_nontemporal_store(hi[1], q + 3);
+    } else {
+        *reinterpret_cast<uint4*>(q) = uint4{lo[0], hi[0], lo[1], hi[1]};
     }
 }
 
