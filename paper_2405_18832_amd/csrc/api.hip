@@ -234,6 +234,11 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
         e = launch_place(*shape, idx, offsets, hist, perm, inv, tokmap, tok * shape->k, hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
     }
+    // One expert per token and every expert running: each row of the permuted order is the whole output of
+    // its token, so the second product scales it by the gate weight and writes `out` directly (Section 2.1's
+    // combine step without the fp32 round trip through memory); otherwise a combine pass follows.
+    const bool folded = shape->k == 1 && used == nullptr && shape->dtype == MOE_BF16;
+    const FoldOut fold{folded ? static_cast<uint16_t*>(out) : nullptr, tokmap, gate};
     if (layer_gathers_kmajor(*shape)) {
         // layers large enough for the tiled kernel: one pass gathers the token rows into the k-step-major
         // layout that lets both kernels fetch operand rows as full cache lines
@@ -241,12 +246,13 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
         e = launch_gather_kmajor(*shape, x, tokmap, xk, hs);
         if (e != hipSuccess) return MOE_ERR_HIP;
         e = launch_expert_products(*shape, xk, nullptr, true, w1, w2, b1, b2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
-                                   hs);
+                                   fold, hs);
     } else {
         e = launch_expert_products(*shape, x, tokmap, false, w1, w2, b1, b2, at<float>(ws, L.y_perm), at<void>(ws, L.h), lists,
-                                   hs);
+                                   fold, hs);
     }
     if (e != hipSuccess) return MOE_ERR_HIP;
+    if (folded) return MOE_OK;                 // the second product has written `out`
     e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
     return from_hip(e);
 }

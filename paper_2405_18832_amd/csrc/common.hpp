@@ -285,6 +285,16 @@ hipError_t launch_select_hot(int E, const int32_t* counts, double alpha, double 
 hipError_t launch_route_fused(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                               int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* gate_part_ws,
                               hipStream_t st);
+// Top-1 layers without an expert mask: the second product writes the layer output itself.  Row p of the
+// permuted order belongs to token tokmap[p] and to nobody else, so out[tokmap[p]] = gate[tokmap[p]] * y[p],
+// rounded to bf16, is the combine step's result for that token (same operations, same rounding) and the
+// fp32 rows of y never go to memory.  out == nullptr: the product writes y as usual.
+struct FoldOut {
+    uint16_t* out;           // [T, N] bf16
+    const int32_t* tokmap;   // [A]
+    const float* gate;       // [T] (k = 1)
+};
+
 // what the finalize kernel needs to place the assignments itself (small layers: one launch less)
 struct PlaceArgs {
     const int32_t* idx;    // nullptr: do not place
@@ -303,13 +313,13 @@ hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* o
 int ffn_tile_rows(const moe_shape& s);
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
                                   const void* w1, const void* w2, const float* b1, const float* b2, float* y_perm,
-                                  void* h_ws, const TileLists& lists, hipStream_t st);
+                                  void* h_ws, const TileLists& lists, const FoldOut& fold, hipStream_t st);
 bool layer_gathers_kmajor(const moe_shape& s);
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
                                float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
-                               const float* bias, hipStream_t st);
+                               const float* bias, const FoldOut& fold, hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
                           const int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* x_perm,

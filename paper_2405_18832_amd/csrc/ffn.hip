@@ -115,11 +115,28 @@ template <> struct StreamPF<2> { static constexpr int value = MOE_PF_TF2; };
 template <> struct StreamPF<3> { static constexpr int value = MOE_PF_TF3; };
 template <> struct StreamPF<4> { static constexpr int value = MOE_PF_TF4; };
 
+// Token row and gate weight of the lane's rows (row fragment tf, row lane % 16) for a folded second product;
+// fetched when a unit starts so that the two dependent loads are long done when the unit's output is stored.
+template <int TFC, bool FOLD>
+__device__ __forceinline__ void fold_rows(const FoldOut& fold, const Tile tl, int (&ftok)[TFC], float (&fw)[TFC]) {
+    const int r = threadIdx.x & 15;
+#pragma unroll
+    for (int tf = 0; tf < TFC; ++tf) {
+        ftok[tf] = 0;
+        fw[tf] = 0.f;
+        if (FOLD) {
+            ftok[tf] = fold.tokmap[tl.row0 + min(tf * 16 + r, tl.rows - 1)];
+            fw[tf] = fold.gate[ftok[tf]];
+        }
+    }
+}
+
 // Output of one column group (4 n-blocks) x TFC row fragments of a tile, by one whole wavefront.
-template <int TFC, int FIRST>
+template <int TFC, int FIRST, bool FOLD>
 __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile tl, const int ng, const int nblk,
                                             const int N, const int rows_total, const float* __restrict__ be,
-                                            const f32x4 (&acc)[4][TFC]) {
+                                            const f32x4 (&acc)[4][TFC], const FoldOut& fold,
+                                            const int (&ftok)[TFC], const float (&fw)[TFC]) {
     const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
 #pragma unroll
     for (int tf = 0; tf < TFC; ++tf) {
@@ -131,6 +148,13 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
                 const int nb = ng * 4 + 2 * m;             // N / 16 is even: the pair exists or not as a whole
                 if (nb >= nblk) continue;                  // wave-uniform
                 store_h_pair<FIRST, true>(outp, tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
+            }
+        } else if constexpr (FOLD) {                       // the layer output itself
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const int nb = ng * 4 + 2 * m;
+                if (nb >= nblk) continue;                  // wave-uniform
+                store_folded_pair(fold.out, ftok[tf], fw[tf], ok, nb * 16, N, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
             }
         } else {
 #pragma unroll
@@ -144,14 +168,14 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
 }
 
 // One wavefront's share of one unit: 4 n-blocks x TFC token fragments over k-steps [kb0, kb1).
-template <int TFC, int TFMAX, int KSPLIT, int FIRST>
+template <int TFC, int TFMAX, int KSPLIT, int FIRST, bool FOLD>
 __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const int32_t* __restrict__ rowmap,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
                                             const int K, const int kb0, const int kb1, f32x4* red,
                                             const int rows_total, const bool act_kmajor,
-                                            const float* __restrict__ bias) {
+                                            const float* __restrict__ bias, const FoldOut& fold) {
     constexpr int PF = StreamPF<TFC>::value;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -164,6 +188,9 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    int ftok[TFC];
+    float fw[TFC];
+    fold_rows<TFC, FOLD>(fold, tl, ftok, fw);
     if (active && kb0 < kb1) {
         const uint16_t* wp[4];
 #pragma unroll
@@ -244,7 +271,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     }
     if (active && ks == 0) {
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        store_group<TFC, FIRST>(outp, tl, ng, nblk, N, rows_total, be, acc);
+        store_group<TFC, FIRST, FOLD>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
     }
     if (KSPLIT > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // `red` may be reused
 }
@@ -255,13 +282,14 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 // row operand out of the vector-memory queue that the weights stream through (one quarter of the
 // requests, issued once, asynchronously) and out of the registers that hold loads in flight.
 // `tok_lds` holds TFC * K / 32 fragments of 1 KiB: fragment (tf, kb) at (tf * K / 32 + kb) * 1024.
-template <int TFC, int FIRST>
+template <int TFC, int FIRST, bool FOLD>
 __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act,
                                                 const int32_t* __restrict__ rowmap,
                                                 const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                                 const Tile tl, const int ng, const bool active, const int N,
                                                 const int K, const int rows_total, const bool act_kmajor,
-                                                const float* __restrict__ bias, unsigned char* tok_lds) {
+                                                const float* __restrict__ bias, unsigned char* tok_lds,
+                                                const FoldOut& fold) {
     constexpr int PF = MOE_PF_LDS;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
@@ -272,6 +300,9 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    int ftok[TFC];
+    float fw[TFC];
+    fold_rows<TFC, FOLD>(fold, tl, ftok, fw);
     // every wavefront has finished reading the previous unit's rows
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // rows -> LDS: wavefront w copies the fragments (tf, kb) with kb = w, w + 4, ...; a lane fetches the
@@ -342,11 +373,11 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
             if (kb + p < kblk) fma(p, kb + p);
 
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        store_group<TFC, FIRST>(outp, tl, ng, nblk, N, rows_total, be, acc);
+        store_group<TFC, FIRST, FOLD>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
     }
 }
 
-template <int TFMAX, int KSPLIT, int FIRST>
+template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
 __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restrict__ act,
                                                          const int32_t* __restrict__ rowmap,
                                                          const uint16_t* __restrict__ wpk,
@@ -357,11 +388,11 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
                                                          int rows_total, int act_kmajor, int rows_in_lds,
-                                                         const float* __restrict__ bias) {
+                                                         const float* __restrict__ bias, const FoldOut fold) {
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total, bias);
+    if (partials != nullptr) finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total, bias, fold);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -396,23 +427,23 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         if (KSPLIT == 1 && rows_in_lds) {
             const bool km = act_kmajor != 0;
             if (TFMAX >= 4 && tfc == 4)
-                stream_unit_lds<4, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
+                stream_unit_lds<4, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
             else if (TFMAX >= 4 && tfc == 3)
-                stream_unit_lds<3, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
+                stream_unit_lds<3, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
             else if (TFMAX >= 2 && tfc == 2)
-                stream_unit_lds<2, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
+                stream_unit_lds<2, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
             else
-                stream_unit_lds<1, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds);
+                stream_unit_lds<1, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
             continue;
         }
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
+            stream_unit<4, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
+            stream_unit<3, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
+            stream_unit<2, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias);
+            stream_unit<1, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
     }
 }
 
@@ -461,12 +492,12 @@ int device_cu_count() {
     return cus[dev];
 }
 
-template <int TFMAX, int KSPLIT, int FIRST>
+template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
                                 const Tile* big_tiles, const float* partials, int rows_total, bool act_kmajor,
-                                const float* bias, hipStream_t st) {
-    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST>;
+                                const float* bias, const FoldOut& fold, hipStream_t st) {
+    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST, FOLD>;
     static int per_cu = 0;
     if (per_cu == 0) {
         int n = 0;
@@ -494,24 +525,41 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), lds, st, act, rowmap, wpk, outp, tiles,
                        ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total,
-                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0, bias);
+                       act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0, bias, fold);
     return hipGetLastError();
 }
 
+template <int TFMAX, int FIRST, bool FOLD>
+static hipError_t launch_stream_kf(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
+                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
+                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
+                                   bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
+    const long ngroups = (N / 16 + 3) / 4;
+    if (ksplit == 4)
+        return launch_stream<TFMAX, 4, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
+                                                    big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
+    if (ksplit == 2)
+        return launch_stream<TFMAX, 2, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+                                                    max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total,
+                                                    act_kmajor, bias, fold, st);
+    return launch_stream<TFMAX, 1, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
+                                                max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total,
+                                                act_kmajor, bias, fold, st);
+}
+
+// the folded form exists for the second product only
 template <int TFMAX, int FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
-                                  bool act_kmajor, const float* bias, hipStream_t st) {
-    const long ngroups = (N / 16 + 3) / 4;
-    if (ksplit == 4)
-        return launch_stream<TFMAX, 4, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                              big_tiles, partials, rows_total, act_kmajor, bias, st);
-    if (ksplit == 2)
-        return launch_stream<TFMAX, 2, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                              max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total, act_kmajor, bias, st);
-    return launch_stream<TFMAX, 1, FIRST>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                          max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total, act_kmajor, bias, st);
+                                  bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
+    if constexpr (FIRST == 0) {
+        if (fold.out != nullptr)
+            return launch_stream_kf<TFMAX, 0, true>(ksplit, act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles,
+                                                    big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
+    }
+    return launch_stream_kf<TFMAX, FIRST, false>(ksplit, act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles,
+                                                 big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -571,7 +619,7 @@ bool layer_gathers_kmajor(const moe_shape& s) {
 
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
                                   const void* w1, const void* w2, const float* b1, const float* b2, float* y_perm,
-                                  void* h_ws, const TileLists& lists, hipStream_t st) {
+                                  void* h_ws, const TileLists& lists, const FoldOut& fold, hipStream_t st) {
     const int A = s.T * s.k, E = s.E, d = s.d_model, f = s.d_ff;
     const int tile_rows = lists.small_rows;
     const Tile* tiles = lists.small_tiles;
@@ -612,30 +660,31 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
     // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
     if (big) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, s.activation, b1, st);
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, s.activation, b1,
+                                  FoldOut{nullptr, nullptr, nullptr}, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
     const bool gelu = s.activation == MOE_ACT_GELU;
     switch (ffn_tfmax(s) * 2 + (gelu ? 1 : 0)) {
-        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
-        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
-        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
-        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
-        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
-        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, st); break;
+        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
     if (big) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, s.activation, b2, st);
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, s.activation, b2, fold, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
-        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
-        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, st); break;
+        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
+        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
+        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);
@@ -653,9 +702,11 @@ hipError_t launch_expert_ffn(const moe_shape& s, const void* x_perm, const void*
     if (layer_gathers_kmajor(s)) {      // large layer: re-lay the permuted rows k-step-major first
         err = launch_gather_kmajor(s, x_perm, nullptr, x_kmajor_ws, st);
         if (err != hipSuccess) return err;
-        return launch_expert_products(s, x_kmajor_ws, nullptr, true, w1, w2, b1, b2, y_perm, h_ws, lists, st);
+        return launch_expert_products(s, x_kmajor_ws, nullptr, true, w1, w2, b1, b2, y_perm, h_ws, lists,
+                                      FoldOut{nullptr, nullptr, nullptr}, st);
     }
-    return launch_expert_products(s, x_perm, nullptr, false, w1, w2, b1, b2, y_perm, h_ws, lists, st);
+    return launch_expert_products(s, x_perm, nullptr, false, w1, w2, b1, b2, y_perm, h_ws, lists,
+                                  FoldOut{nullptr, nullptr, nullptr}, st);
 }
 
 }  // namespace moe

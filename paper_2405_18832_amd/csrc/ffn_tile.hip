@@ -74,7 +74,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        int32_t* __restrict__ part_counter,
                                                        float* __restrict__ partials, int N, int K,
                                                        int rows_total, int act_kmajor,
-                                                       const float* __restrict__ bias) {
+                                                       const float* __restrict__ bias, const FoldOut fold) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // between units, when no stage is in use, the first word of the ring passes the next part's number on
     int* next_part = reinterpret_cast<int*>(smem);
@@ -291,11 +291,26 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                    acc[2 * m + 1][tf]);
                     }
                 } else {
+                    int ftok = 0;
+                    float fw = 0.f;
+                    if (fold.out != nullptr && ok) {                    // folded layer output (top-1, no mask)
+                        ftok = fold.tokmap[cur.tl.row0 + lr];
+                        fw = fold.gate[ftok];
+                    }
+                    if (fold.out != nullptr) {                          // block-uniform
 #pragma unroll
-                    for (int nf = 0; nf < 4; ++nf) {
-                        const int nb = cur.nt * 16 + wn * 4 + nf;
-                        if (ok && nb < nblk)
-                            store_out<0>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                        for (int m = 0; m < 2; ++m) {
+                            const int nb = cur.nt * 16 + wn * 4 + 2 * m;
+                            if (nb >= nblk) continue;                   // wave-uniform
+                            store_folded_pair(fold.out, ftok, fw, ok, nb * 16, N, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int nf = 0; nf < 4; ++nf) {
+                            const int nb = cur.nt * 16 + wn * 4 + nf;
+                            if (ok && nb < nblk)
+                                store_out<0>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                        }
                     }
                 }
             }
@@ -307,7 +322,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 template <int FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                               const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
-                              int K, int rows_total, bool act_kmajor, const float* bias, hipStream_t st) {
+                              int K, int rows_total, bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
     constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
     static bool configured = false;
@@ -321,7 +336,7 @@ static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const 
     // only known on the device, and few units are cut along K over blocks that would otherwise idle.
     const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0, bias);
+                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0, bias, fold);
     return hipGetLastError();
 }
 
@@ -330,15 +345,15 @@ int tile_product_grid() { return device_cu_count(); }
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
                                float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
-                               const float* bias, hipStream_t st) {
+                               const float* bias, const FoldOut& fold, hipStream_t st) {
     if (!first)
         return launch_tile<0>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                              act_kmajor, bias, st);
+                              act_kmajor, bias, fold, st);
     if (activation == MOE_ACT_GELU)
         return launch_tile<kFirstGelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                                       act_kmajor, bias, st);
+                                       act_kmajor, bias, fold, st);
     return launch_tile<kFirstRelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
-                                   act_kmajor, bias, st);
+                                   act_kmajor, bias, fold, st);
 }
 
 }  // namespace moe

@@ -84,6 +84,17 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
     }
 }
 
+// Second-product output of a row whose layer output is written directly (FoldOut): 4 columns n ... n + 3 of
+// out[t], t and the row's gate weight w looked up by the caller.  fmaf(w, y, 0) and one rounding to bf16: what
+// the combine step does for a token with a single expert.
+__device__ __forceinline__ void store_folded(uint16_t* out, int t, float w, int n, int N, const float* bias, f32x4 v) {
+    if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n);
+    uint2 pk;
+    pk.x = pack_bf16x2(fmaf(w, v[0], 0.f), fmaf(w, v[1], 0.f));
+    pk.y = pack_bf16x2(fmaf(w, v[2], 0.f), fmaf(w, v[3], 0.f));
+    *reinterpret_cast<uint2*>(out + static_cast<size_t>(t) * N + n) = pk;
+}
+
 // First-product output of two adjacent 16-column blocks (columns n0 ... n0 + 31: one k-step block of h) for
 // the 16 rows of an accumulator pair.  Called by a whole wavefront (no divergence around it): lane (r, g),
 // r = lane % 16 the row, g = lane / 16, holds columns n0 + 4g ... + 3 in v0 and n0 + 16 + 4g ... + 3 in v1.
@@ -118,13 +129,37 @@ __device__ __forceinline__ void store_h_pair(void* outp, int row, bool row_ok, i
     }
 }
 
+// store_folded for two adjacent 16-column blocks (columns n0 ... n0 + 31) of the 16 rows of an accumulator
+// pair, by a whole wavefront, with the lane exchange of store_h_pair: every lane ends up with 8 consecutive
+// columns of its row, one 16-byte store (64 contiguous bytes per token row and instruction).  The output is
+// not read again by the layer: non-temporal.
+__device__ __forceinline__ void store_folded_pair(uint16_t* out, int t, float w, bool row_ok, int n0, int N,
+                                                  const float* bias, f32x4 v0, f32x4 v1) {
+    const int g = (threadIdx.x & 63) >> 4;
+    if (bias != nullptr) {
+        v0 += *reinterpret_cast<const f32x4*>(bias + n0 + g * 4);
+        v1 += *reinterpret_cast<const f32x4*>(bias + n0 + 16 + g * 4);
+    }
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16x2(fmaf(w, v0[0], 0.f), fmaf(w, v0[1], 0.f)),
+                                                     pack_bf16x2(fmaf(w, v1[0], 0.f), fmaf(w, v1[1], 0.f)), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16x2(fmaf(w, v0[2], 0.f), fmaf(w, v0[3], 0.f)),
+                                                     pack_bf16x2(fmaf(w, v1[2], 0.f), fmaf(w, v1[3], 0.f)), false, false);
+    const int n = n0 + (g & 1) * 16 + (g & 2) * 4;
+    if (!row_ok) return;
+    uint32_t* q = reinterpret_cast<uint32_t*>(out + static_cast<size_t>(t) * N + n);
+    __builtin_nontemporal_store(lo[0], q);                 // merged into one 16-byte store
+    __builtin_nontemporal_store(hi[0], q + 1);
+    __builtin_nontemporal_store(lo[1], q + 2);
+    __builtin_nontemporal_store(hi[1], q + 3);
+}
+
 // Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
 // Called by every thread of every block of the following kernel; 4 columns of a row per thread and step.
-template <int FIRST>
+template <int FIRST, bool FOLD>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
                                                    int N, int kblk, int G, int rows_total,
-                                                   const float* __restrict__ bias) {
+                                                   const float* __restrict__ bias, const FoldOut fold) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
@@ -142,8 +177,13 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
         f32x4 sum = *reinterpret_cast<const f32x4*>(base);
         for (int p = 1; p < s.split; ++p)
             sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
-        store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total,
-                         bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr, sum);
+        const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
+        if constexpr (FOLD) {
+            const int t = fold.tokmap[tl.row0 + lr];
+            store_folded(fold.out, t, fold.gate[t], c, N, be, sum);
+        } else {
+            store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, be, sum);
+        }
     }
 }
 #endif
