@@ -86,6 +86,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
     const int nblk = N >> 4, kblk = K >> 5;
     const int ntn = (N + kTN - 1) / kTN;
     const int ntiles = ntiles_p[0];
+    if (ntiles <= 0) return;                            // no large expert in this call (block-uniform)
     // LDS byte address of the first of the two fragments that this wavefront copies in, stage 0
     const uint32_t copy_base = lds_address(smem) + 2 * wave * 1024;
 

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void perm_hist_kernel(const int32_t* __restric
     }
     __syncthreads();
     if (c < nchunks)
-        for (int e = lane; e < E; e += 64) hist[static_cast<size_t>(e) * nchunks + c] = h[wave][e];
+        for (int e = lane; e < E; e += 64) hist[static_cast<size_t>(c) * E + e] = h[wave][e];
 }
 
 // kernel 3: place the chunk's assignments (kernel 2, the prefix sum over chunks, is
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void perm_place_kernel(const int32_t* __restri
     const int c = blockIdx.x * 4 + wave;
     if (c >= nchunks) return;                   // no block-wide barrier below: waves are independent
     int32_t* next = next_all[wave];
-    for (int e = lane; e < E; e += 64) next[e] = offsets[e] + chunk_base[static_cast<size_t>(e) * nchunks + c];
+    for (int e = lane; e < E; e += 64) next[e] = offsets[e] + chunk_base[static_cast<size_t>(c) * E + e];
     __builtin_amdgcn_wave_barrier();
     place_chunk(idx, next, perm, inv_perm, tokmap, A, E, k, ebits, chunk, c);
 }

@@ -21,43 +21,87 @@ constexpr int kMaxRounds = MOE_MAX_K + 1;
 // lane-local scan and in every exchange, so the order is "descending logit, ties by lowest
 // expert index".  A winner is retired by overwriting its logit with -inf.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, int k, int renorm, int sub,
-                                              bool live, int32_t* __restrict__ idx_out,
-                                              float* __restrict__ w_out, float* __restrict__ margin_out,
-                                              int32_t* __restrict__ hist) {
+// Value of the lane n places away inside the lane's row of 16 (a DPP row rotation, no LDS traffic).  Four
+// steps with n = 8, 4, 2, 1 leave every lane of the row with the reduction over the row; for sums the
+// operand pairs are those of the xor butterfly (after a step with n the values have period n in the row).
+template <int N>
+__device__ __forceinline__ float row_rot(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xF, 0xF, false));
+}
+template <int N>
+__device__ __forceinline__ int row_rot(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xF, 0xF, false);
+}
+
+// V > 0: the row has at most 16 * V experts and the lane keeps its V logits (experts sub, sub + 16, ...) in
+// registers for all rounds; V == 0: any E, the row is read from LDS in every round and a winner is retired by
+// overwriting its logit there.  (Every LDS read in the per-round loops is a round trip the next compare waits
+// for: with the row in registers the top-k of a 64-token chunk of 128 experts takes a third of the time.)
+template <int V>
+__device__ __forceinline__ void topk_row(float* __restrict__ row, int E, int k, int renorm, int sub, bool live,
+                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
+                                         float* __restrict__ margin_out, int32_t* __restrict__ hist) {
     const float NEG = -__builtin_huge_valf();
     float sel_v[kMaxRounds];
     int sel_i[kMaxRounds];
-    const int rounds = min(k + 1, E);
+    const int rounds = min(k + (margin_out != nullptr ? 1 : 0), E);   // the margin needs one more winner
     float vmax = 0.f, denom = 1.f;
+    float v[V > 0 ? V : 1];
+    if constexpr (V > 0) {
+#pragma unroll
+        for (int q = 0; q < V; ++q) v[q] = (sub + 16 * q < E) ? row[sub + 16 * q] : NEG;
+    }
 #pragma unroll 1
     for (int j = 0; j < rounds; ++j) {
         float bv = NEG;
         int bi = 0x7fffffff;
-        for (int e = sub; e < E; e += 16) {
-            const float v = row[e];
-            if (v > bv || bi == 0x7fffffff) { bv = v; bi = e; }
-        }
+        if constexpr (V > 0) {
 #pragma unroll
-        for (int s = 8; s >= 1; s >>= 1) {
-            const float ov = __shfl_xor(bv, s);
-            const int oi = __shfl_xor(bi, s);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            for (int q = 0; q < V; ++q) {
+                const int e = sub + 16 * q;
+                if (e < E && (v[q] > bv || bi == 0x7fffffff)) { bv = v[q]; bi = e; }
+            }
+        } else {
+            for (int e = sub; e < E; e += 16) {
+                const float x = row[e];
+                if (x > bv || bi == 0x7fffffff) { bv = x; bi = e; }
+            }
         }
+        auto better = [&](float ov, int oi) {
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        };
+        better(row_rot<8>(bv), row_rot<8>(bi));
+        better(row_rot<4>(bv), row_rot<4>(bi));
+        better(row_rot<2>(bv), row_rot<2>(bi));
+        better(row_rot<1>(bv), row_rot<1>(bi));
         bi = min(bi, E - 1);          // NaN logits must not produce an out-of-range expert
         if (j == 0) {
             vmax = bv;
             float part = 0.f;
-            for (int e = sub; e < E; e += 16) part += expf(row[e] - vmax);
+            if constexpr (V > 0) {
 #pragma unroll
-            for (int s = 8; s >= 1; s >>= 1) part += __shfl_xor(part, s);
+                for (int q = 0; q < V; ++q)
+                    if (sub + 16 * q < E) part += expf(v[q] - vmax);
+            } else {
+                for (int e = sub; e < E; e += 16) part += expf(row[e] - vmax);
+            }
+            part += row_rot<8>(part);
+            part += row_rot<4>(part);
+            part += row_rot<2>(part);
+            part += row_rot<1>(part);
             denom = part;
         }
 #pragma unroll
         for (int q = 0; q < kMaxRounds; ++q)
             if (q == j) { sel_v[q] = bv; sel_i[q] = bi; }
-        if (sub == 0) row[bi] = NEG;
-        __builtin_amdgcn_wave_barrier();
+        if constexpr (V > 0) {
+#pragma unroll
+            for (int q = 0; q < V; ++q)
+                if (sub + 16 * q == bi) v[q] = NEG;
+        } else {
+            if (sub == 0) row[bi] = NEG;
+            __builtin_amdgcn_wave_barrier();
+        }
     }
     if (live && sub == 0) {
         float p[MOE_MAX_K];
@@ -85,6 +129,21 @@ __device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, in
     }
 }
 
+// called by whole wavefronts; E is uniform
+__device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, int k, int renorm, int sub,
+                                              bool live, int32_t* __restrict__ idx_out,
+                                              float* __restrict__ w_out, float* __restrict__ margin_out,
+                                              int32_t* __restrict__ hist) {
+    if (E <= 64) topk_row<4>(row, E, k, renorm, sub, live, idx_out, w_out, margin_out, hist);
+    else if (E <= 128) topk_row<8>(row, E, k, renorm, sub, live, idx_out, w_out, margin_out, hist);
+    else if (E <= 256) topk_row<16>(row, E, k, renorm, sub, live, idx_out, w_out, margin_out, hist);
+    else topk_row<0>(row, E, k, renorm, sub, live, idx_out, w_out, margin_out, hist);
+}
+
+// Floats per token row of the logits in LDS: whole groups of 16 * NF experts (the accumulate step writes
+// full fragments) plus 4, which keeps the rows 16-byte aligned and moves consecutive rows to different banks.
+__host__ __device__ inline int route_row_stride(int E, int NF) { return (E + 16 * NF - 1) / (16 * NF) * (16 * NF) + 4; }
+
 // ---------------------------------------------------------------------------
 // route_fused_kernel<ST, TF, NW, NF>: block = NW wavefronts, chunk = 16*TF tokens.
 //  bf16: MFMA 16x16x32 with gate rows as the A operand and token rows as the B operand (a lane
@@ -94,8 +153,8 @@ __device__ __forceinline__ void topk_from_lds(float* __restrict__ row, int E, in
 //  into LDS one after the other, in wave order (deterministic).  Every k-step issues exactly
 //  NF + TF loads (rows past the end are clamped, their results dropped), two steps ahead.
 //  fp32: plain FMA dot products, one (token, expert) pair per thread and pass.
-// The chunk's histogram goes to chunk_hist[e * nchunks + chunk].
-// Dynamic LDS: logits [16*TF][E+1] floats, then the histogram [E] ints.
+// The chunk's histogram goes to chunk_hist[chunk * E + e].
+// Dynamic LDS: logits [16*TF][route_row_stride(E, NF)] floats, then the histogram [E] ints.
 // ---------------------------------------------------------------------------
 template <typename ST, int TF, int NW, int NF>
 __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restrict__ x, const ST* __restrict__ wg,
@@ -107,8 +166,8 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
                                                               int E, int k, int renorm) {
     constexpr int TOK = 16 * TF;
     constexpr int NT = NW * 64;
-    extern __shared__ float lds[];
-    const int Ep = E + 1;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int Ep = route_row_stride(E, NF);
     float* L = lds;
     int32_t* hist = reinterpret_cast<int32_t*>(lds + TOK * Ep);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -172,21 +231,35 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
                 for (int p = 0; p < PF; ++p)
                     if (kb + p < kb1) fma(p);
             }
-            for (int w = 0; w < NW; ++w) {       // partial sums are added in wave order: deterministic
+            // Partial sums are added in wave order (deterministic).  The wavefront whose turn it is reads all
+            // the sums so far as 16-byte pieces (a lane's 4 experts of a token are adjacent), then writes them
+            // back: one LDS latency per turn.  Rows are padded to whole fragments, so nothing here depends on E.
+            f32x4 first[NF];                               // what the first wavefront starts from: the bias
+#pragma unroll
+            for (int nf = 0; nf < NF; ++nf) {
+                first[nf] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (bias != nullptr && wave == 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) first[nf][i] = bias[min(ec + nf * 16 + g * 4 + i, E - 1)];
+                }
+            }
+            for (int w = 0; w < NW; ++w) {
                 if (wave == w) {
+                    f32x4 sofar[NF][TF];
 #pragma unroll
                     for (int nf = 0; nf < NF; ++nf)
 #pragma unroll
-                        for (int tf = 0; tf < TF; ++tf)
+                        for (int tf = 0; tf < TF; ++tf) {
+                            const f32x4* p = reinterpret_cast<const f32x4*>(L + (tf * 16 + r) * Ep + ec + nf * 16 + g * 4);
+                            sofar[nf][tf] = (w == 0) ? first[nf] : *p;
+                        }
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int e = ec + nf * 16 + g * 4 + i;
-                                if (e < E) {
-                                    float* p = L + (tf * 16 + r) * Ep + e;
-                                    const float v = acc[nf][tf][i];
-                                    *p = (w == 0) ? v + (bias ? bias[e] : 0.f) : *p + v;
-                                }
-                            }
+                    for (int nf = 0; nf < NF; ++nf)
+#pragma unroll
+                        for (int tf = 0; tf < TF; ++tf) {
+                            f32x4* p = reinterpret_cast<f32x4*>(L + (tf * 16 + r) * Ep + ec + nf * 16 + g * 4);
+                            *p = acc[nf][tf] + sofar[nf][tf];
+                        }
                 }
                 __syncthreads();
             }
@@ -215,7 +288,7 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
     }
     __syncthreads();
     const int nchunks = gridDim.x;
-    for (int e = threadIdx.x; e < E; e += NT) chunk_hist[static_cast<size_t>(e) * nchunks + blockIdx.x] = hist[e];
+    for (int e = threadIdx.x; e < E; e += NT) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
 }
 
 // ---------------------------------------------------------------------------
@@ -240,37 +313,59 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
     __shared__ int32_t place_next[16][kScanPlaceMaxE];   // per wavefront: next free slot of every expert
+    __shared__ int32_t group_total[1024];                // phase 1: [group][expert] sums over a group's chunks
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    // phase 1: wavefront w owns experts w, w+16, ...; it walks them 8 at a time so that the 8 rows'
-    // loads are in flight together (chunk_hist is [E][nchunks]: a row is contiguous)
-    for (int eb = wave; eb < E; eb += 16 * 8) {
-        int carry[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) carry[j] = 0;
-        for (int c0 = 0; c0 < nchunks; c0 += 64) {
-            const int c = c0 + lane;
+    // phase 1: chunk_hist is [nchunks][E], so threads that take consecutive experts of one chunk read and
+    // write contiguously.  The block is cut into ngrp = 1024 / Ew groups of Ew threads (Ew = E rounded up to
+    // whole wavefronts); group q owns the chunks [q * seg, (q + 1) * seg), adds them up per expert 8 loads at
+    // a time, the group totals meet in LDS, and the segment is rewritten with its exclusive prefix sums (kept
+    // in registers between the two sweeps when it has at most 8 chunks, else read again from L2).  (One
+    // shuffle scan of 6 steps per 64 chunks and expert, as before, cost 5.5 us on 64 experts x 128 chunks:
+    // the shuffles are LDS round trips that wait for one another.)
+    {
+        const int Ew = min(1024, (E + 63) & ~63), ngrp = 1024 / Ew;
+        const int q = threadIdx.x / Ew, ex = threadIdx.x - q * Ew;
+        const bool have = q < ngrp && ex < E;              // threads past ngrp * Ew (none when Ew divides 1024)
+        const int seg = (nchunks + ngrp - 1) / ngrp;
+        const int c_begin = min(q * seg, nchunks), c_end = min(c_begin + seg, nchunks);
+        int32_t* col = chunk_hist + (have ? ex : 0);
+        int first[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int total = 0;
+        for (int c0 = c_begin; c0 < c_end; c0 += 8) {
             int v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int e = eb + 16 * j;
-                v[j] = (e < E && c < nchunks) ? chunk_hist[static_cast<size_t>(e) * nchunks + c] : 0;
-            }
+            for (int i = 0; i < 8; ++i) v[i] = (have && c0 + i < c_end) ? col[static_cast<size_t>(c0 + i) * E] : 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int e = eb + 16 * j;
-                int incl = v[j];
-#pragma unroll
-                for (int s = 1; s < 64; s <<= 1) {
-                    const int o = __shfl_up(incl, s);
-                    if (lane >= s) incl += o;
-                }
-                if (e < E && c < nchunks) chunk_hist[static_cast<size_t>(e) * nchunks + c] = carry[j] + incl - v[j];
-                carry[j] += __shfl(incl, 63);
+            for (int i = 0; i < 8; ++i) {
+                if (c0 == c_begin) first[i] = v[i];
+                total += v[i];
             }
         }
+        if (have) group_total[q * Ew + ex] = total;
+        __syncthreads();
+        int carry = 0;                                     // chunks of the groups before this one
+        if (have) {
+            for (int o = 0; o < q; ++o) carry += group_total[o * Ew + ex];
+            if (q == ngrp - 1) cnt[ex] = carry + total;
+        }
+        if (seg <= 8) {                                    // block-uniform
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (lane == 0 && eb + 16 * j < E) cnt[eb + 16 * j] = carry[j];
+            for (int i = 0; i < 8; ++i) {
+                if (have && c_begin + i < c_end) col[static_cast<size_t>(c_begin + i) * E] = carry;
+                carry += first[i];
+            }
+        } else {
+            for (int c0 = c_begin; c0 < c_end; c0 += 8) {
+                int v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = (have && c0 + i < c_end) ? col[static_cast<size_t>(c0 + i) * E] : 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    if (have && c0 + i < c_end) col[static_cast<size_t>(c0 + i) * E] = carry;
+                    carry += v[i];
+                }
+            }
+        }
     }
     __syncthreads();
     const int e = threadIdx.x;
@@ -304,7 +399,7 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
     while ((1 << ebits) < E) ++ebits;
     int32_t* next = place_next[wave];
     for (int c = wave; c < nchunks; c += 16) {
-        for (int x = lane; x < E; x += 64) next[x] = cnt[x] + chunk_hist[static_cast<size_t>(x) * nchunks + c];
+        for (int x = lane; x < E; x += 64) next[x] = cnt[x] + chunk_hist[static_cast<size_t>(c) * E + x];
         __builtin_amdgcn_wave_barrier();
         place_chunk(place.idx, next, place.perm, place.inv_perm, place.tokmap, place.A, E, place.k, ebits,
                     place.chunk, c);
@@ -388,7 +483,7 @@ static hipError_t launch_route_inst(const moe_shape& s, const void* x, const voi
                                     int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
     constexpr int tok = 16 * TF;
     const unsigned grid = static_cast<unsigned>((s.T + tok - 1) / tok);
-    const size_t lds = static_cast<size_t>(tok) * (s.E + 1) * 4 + static_cast<size_t>(s.E) * 4;
+    const size_t lds = static_cast<size_t>(tok) * route_row_stride(s.E, NF) * 4 + static_cast<size_t>(s.E) * 4;
     auto kern = route_fused_kernel<ST, TF, NW, NF>;
     if (lds > 48 * 1024) {      // more LDS than the default per-block limit: raise it for this kernel
         hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -484,7 +579,7 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
                   margin ? margin + (live ? t : 0) : nullptr, hist);
     __syncthreads();
     const int nchunks = gridDim.x;
-    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(e) * nchunks + blockIdx.x] = hist[e];
+    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
 }
 
 static hipError_t launch_route_small(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
