@@ -41,6 +41,7 @@ class HipEvents:
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 
     def create(self):
         ev = ctypes.c_void_p()
@@ -54,6 +55,10 @@ class HipEvents:
             raise RuntimeError("hipEventElapsedTime failed")
         return float(ms.value)
 
+    def record(self, ev, stream):
+        if self.hip.hipEventRecord(ev, ctypes.c_void_p(stream)) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
     def destroy(self, ev):
         self.hip.hipEventDestroy(ev)
 
@@ -61,13 +66,13 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "e6c7e22ab25c3780", "ffn_tile.hip": "a697a5158a9492b5",
-                   "tile_schedule.hpp": "dc1e57eac5a84857", "common.hpp": "9b240c5d89192dea"}
+TRAFFIC_SOURCES = {"ffn.hip": "76ca1c968d1d59a7", "ffn_tile.hip": "d6e05b7ff0696246",
+                   "tile_schedule.hpp": "cfb38ed553932c2c", "common.hpp": "0cbda28b4f9aeb0c"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 321829707, ("switch_base", "stream_w2"): 321695745,
-    ("nllb_decode", "stream_w1"): 1644094470, ("nllb_decode", "stream_w2"): 1645611771,
-    ("nllb_prefill_skew", "stream_w1"): 1164126682, ("nllb_prefill_skew", "stream_w2"): 1152682864,
-    ("nllb_prefill_skew", "tile_w1"): 2522962368, ("nllb_prefill_skew", "tile_w2"): 2208274900,
+    ("switch_base", "stream_w1"): 316954598, ("switch_base", "stream_w2"): 320734056,
+    ("nllb_decode", "stream_w1"): 1643996952, ("nllb_decode", "stream_w2"): 1645964734,
+    ("nllb_prefill_skew", "stream_w1"): 1159055731, ("nllb_prefill_skew", "stream_w2"): 1152843533,
+    ("nllb_prefill_skew", "tile_w1"): 2488044696, ("nllb_prefill_skew", "tile_w2"): 2217428334,
 }
 
 
@@ -178,13 +183,22 @@ def main() -> int:
     hev = HipEvents()
     evs = [[hev.create() for _ in range(5)] for _ in range(K)]
     torch.cuda.synchronize()
+    # Two events recorded back to back, with nothing between them, are already some microseconds apart (the
+    # second event's own packet): that interval is measured after every step, on the same stream, and taken
+    # off each kernel's interval, which then agrees with the kernel durations rocprofv3 reports.
+    gap = [[hev.create(), hev.create()] for _ in range(K)]
+    stream = torch.cuda.current_stream().cuda_stream
     for i in range(K):
         moe.moe_set_profile_events(evs[i])
         L.forward(H=H, copy=i)
+        hev.record(gap[i][0], stream)
+        hev.record(gap[i][1], stream)
     moe.moe_set_profile_events(None)
     torch.cuda.synchronize()
-    seg = np.array([[hev.elapsed_ms(e[j], e[j + 1]) for j in range(4)] for e in evs]) * 1e3      # us
-    for e5 in evs:
+    seg_raw = np.array([[hev.elapsed_ms(e[j], e[j + 1]) for j in range(4)] for e in evs]) * 1e3      # us
+    ev_gap = float(np.median([hev.elapsed_ms(a, z) for a, z in gap])) * 1e3
+    seg = np.maximum(seg_raw - ev_gap, 0.0)
+    for e5 in evs + gap:
         for e in e5:
             hev.destroy(e)
 
@@ -223,7 +237,7 @@ def main() -> int:
         rows, wb = (rows_b, wb_b) if j % 2 == 0 else (rows_s, wb_s)
         io = rows * d * (es if j < 2 else 4)                 # rows in (first product) / fp32 rows out (second)
         kern.append(dict(name=names[j], tag=tags[j], us=float(seg[:, j].mean()), us_min=float(seg[:, j].min()),
-                         bytes=wb + io, flops=2.0 * rows * d * f))
+                         us_raw=float(seg_raw[:, j].mean()), bytes=wb + io, flops=2.0 * rows * d * f))
     kd = max(kern, key=lambda q: q["us"])
     t_flop = kd["flops"] / (PEAK_BF16_TFLOPS * 1e12)
     t_byte = kd["bytes"] / (PEAK_HBM_GBPS * 1e9)
@@ -240,6 +254,7 @@ def main() -> int:
                 "frac": ach / PEAK_HBM_GBPS, "traffic": traffic}
     if roof is not None:
         roof.update(kernel=kd["name"], kernel_us=kd["us"], kernel_us_min=kd["us_min"],
+                    kernel_us_between_events=kd["us_raw"], empty_event_interval_us=ev_gap,
                     algorithmic_bytes=kd["bytes"], flops=kd["flops"],
                     ffn_kernels_us={q["tag"]: round(q["us"], 2) for q in kern})
 
