@@ -12,7 +12,7 @@
 
 namespace moe {
 
-// kernel 1: hist[e][chunk] = number of assignments of expert e inside the chunk.
+// kernel 1: hist[chunk][e] = number of assignments of expert e inside the chunk.
 // One wavefront per chunk, 4 chunks per block.
 __global__ __launch_bounds__(256) void perm_hist_kernel(const int32_t* __restrict__ idx,
                                                         int32_t* __restrict__ hist, int A, int E,

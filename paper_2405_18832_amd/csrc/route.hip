@@ -15,12 +15,6 @@ namespace moe {
 
 constexpr int kMaxRounds = MOE_MAX_K + 1;
 
-// ---------------------------------------------------------------------------
-// top-k of one token from its logits row in LDS, by a group of 16 lanes (4 tokens per wave).
-// k+1 rounds of a (value, index) arg-max; on equal values the lower index wins, in the
-// lane-local scan and in every exchange, so the order is "descending logit, ties by lowest
-// expert index".  A winner is retired by overwriting its logit with -inf.
-// ---------------------------------------------------------------------------
 // Value of the lane n places away inside the lane's row of 16 (a DPP row rotation, no LDS traffic).  Four
 // steps with n = 8, 4, 2, 1 leave every lane of the row with the reduction over the row; for sums the
 // operand pairs are those of the xor butterfly (after a step with n the values have period n in the row).
@@ -33,6 +27,12 @@ __device__ __forceinline__ int row_rot(int v) {
     return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xF, 0xF, false);
 }
 
+// ---------------------------------------------------------------------------
+// top-k of one token from its logits row in LDS, by a group of 16 lanes (4 tokens per wave).
+// k rounds (k + 1 when the margin is wanted) of a (value, index) arg-max; on equal values the
+// lower index wins, in the lane-local scan and in every exchange, so the order is "descending
+// logit, ties by lowest expert index".  A winner is retired by setting its logit to -inf.
+// ---------------------------------------------------------------------------
 // V > 0: the row has at most 16 * V experts and the lane keeps its V logits (experts sub, sub + 16, ...) in
 // registers for all rounds; V == 0: any E, the row is read from LDS in every round and a winner is retired by
 // overwriting its logit there.  (Every LDS read in the per-round loops is a round trip the next compare waits
