@@ -19,35 +19,52 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + wave;
     if (t >= T) return;
+    // The token's k rows, by slot; a slot whose expert is masked out (or invalid) is skipped.  Everything is
+    // indexed by compile-time slot numbers (a compacted list would be indexed dynamically and its loads would
+    // be issued and waited for one by one), and the slots that count are added in ascending order.
     const float* rows[MOE_MAX_K];
     float w[MOE_MAX_K];
-    int n = 0;
-    for (int j = 0; j < k; ++j) {
-        const int a = t * k + j;
-        const int e = idx[a];
-        const int p = inv_perm[a];
-        const bool on = (e >= 0 && e < E && p >= 0 && p < A) && (mask == nullptr || mask[e] != 0);
-        if (on) {
-            rows[n] = y_perm + static_cast<size_t>(p) * d;
-            w[n] = gate[a];
-            ++n;
+    bool on[MOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+        rows[j] = y_perm;
+        w[j] = 0.f;
+        on[j] = false;
+        if (j < k) {
+            const int a = t * k + j;
+            const int e = idx[a];
+            const int p = inv_perm[a];
+            on[j] = (e >= 0 && e < E && p >= 0 && p < A) && (mask == nullptr || mask[e] != 0);
+            if (on[j]) {
+                rows[j] = y_perm + static_cast<size_t>(p) * d;
+                w[j] = gate[a];
+            }
         }
     }
     ST* o = out + static_cast<size_t>(t) * d;
     for (int c = lane * VEC; c < d; c += 64 * VEC) {
+        float v[MOE_MAX_K][VEC];
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {              // all the loads of the step first
+            if (!on[j]) continue;                          // wave-uniform: one token per wavefront
+            if (VEC == 4) {
+                const float4 q = *reinterpret_cast<const float4*>(rows[j] + c);
+                v[j][0] = q.x;
+                v[j][1 % VEC] = q.y;
+                v[j][2 % VEC] = q.z;
+                v[j][3 % VEC] = q.w;
+            } else {
+                v[j][0] = rows[j][c];
+            }
+        }
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-        for (int j = 0; j < n; ++j) {
-            if (VEC == 4) {
-                const float4 v = *reinterpret_cast<const float4*>(rows[j] + c);
-                acc[0] = fmaf(w[j], v.x, acc[0]);
-                acc[1] = fmaf(w[j], v.y, acc[1]);
-                acc[2] = fmaf(w[j], v.z, acc[2]);
-                acc[3] = fmaf(w[j], v.w, acc[3]);
-            } else {
-                acc[0] = fmaf(w[j], rows[j][c], acc[0]);
-            }
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {
+            if (!on[j]) continue;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w[j], v[j][i], acc[i]);
         }
 #pragma unroll
         for (int i = 0; i < VEC; ++i) Storage<ST>::store(o + c + i, acc[i]);

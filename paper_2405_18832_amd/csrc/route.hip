@@ -562,12 +562,30 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int t0 = blockIdx.x * 16;
     for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
-    for (int i = threadIdx.x; i < 16 * E; i += 256) {
-        const int tl = i / E, e = i - tl * E;
-        const int t = min(t0 + tl, Tpad - 1);
-        float s = bias ? bias[e] : 0.f;
-        for (int ks = 0; ks < kGateSplit; ++ks) s += part[(static_cast<size_t>(ks) * Tpad + t) * E + e];   // fixed order
-        L[tl * Ep + e] = s;
+    // 4 logits per thread and pass: their 4 * kGateSplit partial sums are loaded before any is added (a wait
+    // per logit otherwise: this kernel is two blocks of pure latency on the decode path)
+    for (int i0 = threadIdx.x; i0 < 16 * E; i0 += 4 * 256) {
+        float p[4][kGateSplit];
+        float b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + u * 256, 16 * E - 1);   // past the end: re-read, not stored
+            const int tl = i / E, e = i - tl * E;
+            const int t = min(t0 + tl, Tpad - 1);
+            b[u] = bias ? bias[e] : 0.f;
+#pragma unroll
+            for (int ks = 0; ks < kGateSplit; ++ks) p[u][ks] = part[(static_cast<size_t>(ks) * Tpad + t) * E + e];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * 256;
+            if (i >= 16 * E) break;
+            const int tl = i / E, e = i - tl * E;
+            float s = b[u];
+#pragma unroll
+            for (int ks = 0; ks < kGateSplit; ++ks) s += p[u][ks];      // fixed order
+            L[tl * Ep + e] = s;
+        }
     }
     __syncthreads();
     const int grp = lane >> 4, sub = lane & 15;
