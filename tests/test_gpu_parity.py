@@ -388,6 +388,30 @@ def test_layer_forward(gpu_lib, name):
     assert torch.equal(a.view(torch.uint8), L.out.view(torch.uint8))
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["one_expert", "all_to_one", "bias_all_to_one", "switch_base", "switch_base_8",
+                                  "switch_large_skew"])
+def test_folded_combine_is_the_combine(gpu_lib, name):
+    """Top-1 layers without a mask let the second product write the layer output (gate weight times the row,
+    rounded once).  With an all-ones mask the same layer takes the separate combine pass (Section 2.1: outputs
+    are combined and put back in token order).  Both do the same multiply and the same rounding on the same
+    fp32 rows, so the outputs must agree bit for bit: streaming kernel, tiled kernel and the tiles that are cut
+    along the contraction and added up by the following kernel."""
+    cfg = CFG(name)
+    assert cfg.k == 1
+    say(f"[case] folded combine {name}")
+    L = device_layer(gpu_lib, name)
+    L.out.fill_(float("nan"))
+    L.forward()
+    torch.cuda.synchronize()
+    folded = L.out.clone()
+    assert torch.isfinite(folded.float()).all()
+    L.out.fill_(float("nan"))
+    L.forward(mask=torch.ones(cfg.E, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(folded.view(torch.uint8), L.out.view(torch.uint8))
+
+
 # ------------------------------------------------------------------------------ hot-set size (Eq. 6)
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", ["tiny_f32", "many_experts", "max_experts", "switch_large_skew", "nllb_decode",
