@@ -64,6 +64,12 @@ EXTRA = {
     "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
                                renormalize=False, seed=17, zipf_s=40.0),
     "switch_large_skew_matched": wl.matched_noise(wl.CONFIGS["switch_large_skew"]),
+    # token counts between the presets: the routing kernel's 32-tokens-per-block form (8192 ... 16383 tokens on a
+    # 256-CU device) and a top-1 layer of that size (folded output, tiled and streaming experts together)
+    "tokens_8k": wl.MoEConfig("tokens_8k", T=8192 + 40, d_model=128, d_ff=256, E=96, k=2, dtype="bf16",
+                              renormalize=True, seed=41, zipf_s=1.1, gate_std=0.3),
+    "tokens_12k_top1": wl.MoEConfig("tokens_12k_top1", T=12000, d_model=128, d_ff=256, E=40, k=1, dtype="bf16",
+                                    renormalize=False, seed=42, zipf_s=1.2, gate_std=0.3),
     # GeLU as the trailing activation (Section 3.4): fp32 kernel, streaming kernel (rows in LDS / split
     # contraction), tiled kernel incl. its K-cut last round
     "gelu_f32": wl.MoEConfig("gelu_f32", T=64, d_model=64, d_ff=256, E=8, k=2, dtype="f32", renormalize=True,
@@ -96,7 +102,8 @@ def CFG(name):
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
          "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
          "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"]
-MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128"]
+MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128",
+          "tokens_8k", "tokens_12k_top1"]
 LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4"]
 
 _layers = {}
@@ -390,7 +397,7 @@ def test_layer_forward(gpu_lib, name):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", ["one_expert", "all_to_one", "bias_all_to_one", "switch_base", "switch_base_8",
-                                  "switch_large_skew"])
+                                  "switch_large_skew", "tokens_12k_top1"])
 def test_folded_combine_is_the_combine(gpu_lib, name):
     """Top-1 layers without a mask let the second product write the layer output (gate weight times the row,
     rounded once).  With an all-ones mask the same layer takes the separate combine pass (Section 2.1: outputs
