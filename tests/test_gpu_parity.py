@@ -59,6 +59,9 @@ EXTRA = {
                                renormalize=True, seed=15, gate_std=0.3),
     "many_experts": wl.MoEConfig("many_experts", T=600, d_model=64, d_ff=64, E=300, k=2, dtype="bf16",
                                  renormalize=True, seed=16, gate_std=0.5),
+    # 129 ... 256 experts: the top-k keeps 16 logits per lane in registers
+    "experts_200": wl.MoEConfig("experts_200", T=500, d_model=64, d_ff=64, E=200, k=4, dtype="bf16",
+                                renormalize=True, seed=19, gate_std=0.5),
     "max_experts": wl.MoEConfig("max_experts", T=50, d_model=32, d_ff=32, E=1024, k=8, dtype="bf16",
                                 renormalize=True, seed=18, gate_std=0.5),
     "all_to_one": wl.MoEConfig("all_to_one", T=200, d_model=64, d_ff=128, E=8, k=1, dtype="bf16",
@@ -100,7 +103,7 @@ def CFG(name):
 
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
-         "many_experts", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
+         "many_experts", "experts_200", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
          "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"]
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128",
           "tokens_8k", "tokens_12k_top1"]
