@@ -100,6 +100,9 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
 #ifndef MOE_PF_TF4
 #define MOE_PF_TF4 3      // ... tiles of <= 64 rows
 #endif
+#ifndef MOE_PF_NARROW
+#define MOE_PF_NARROW 16  // ... when a wavefront owns one column block only (one KiB of weights per step)
+#endif
 #ifndef MOE_PF_LDS
 #define MOE_PF_LDS 6      // k-steps of weight loads in flight when the rows come from LDS
 #endif
@@ -132,24 +135,25 @@ __device__ __forceinline__ void fold_rows(const FoldOut& fold, const Tile tl, in
 }
 
 // Output of one column group (4 n-blocks) x TFC row fragments of a tile, by one whole wavefront.
-template <int TFC, int FIRST, bool FOLD>
+template <int TFC, int FIRST, bool FOLD, int GW = 4>
 __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile tl, const int ng, const int nblk,
                                             const int N, const int rows_total, const float* __restrict__ be,
-                                            const f32x4 (&acc)[4][TFC], const FoldOut& fold,
+                                            const f32x4 (&acc)[GW][TFC], const FoldOut& fold,
                                             const int (&ftok)[TFC], const float (&fw)[TFC]) {
+    static_assert(GW == 4 || (FIRST == 0 && !FOLD), "paired stores need groups of 4 column blocks");
     const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
 #pragma unroll
     for (int tf = 0; tf < TFC; ++tf) {
         const int lr = tf * 16 + r;
         const bool ok = lr < tl.rows;
-        if constexpr (FIRST != 0) {
+        if constexpr (FIRST != 0 && GW == 4) {
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 const int nb = ng * 4 + 2 * m;             // N / 16 is even: the pair exists or not as a whole
                 if (nb >= nblk) continue;                  // wave-uniform
                 store_h_pair<FIRST, true>(outp, tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
             }
-        } else if constexpr (FOLD) {                       // the layer output itself
+        } else if constexpr (FOLD && GW == 4) {            // the layer output itself
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 const int nb = ng * 4 + 2 * m;
@@ -158,8 +162,8 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
             }
         } else {
 #pragma unroll
-            for (int nf = 0; nf < 4; ++nf) {
-                const int nb = ng * 4 + nf;
+            for (int nf = 0; nf < GW; ++nf) {
+                const int nb = ng * GW + nf;
                 if (ok && nb < nblk)
                     store_out<0, true>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
             }
@@ -168,7 +172,7 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
 }
 
 // One wavefront's share of one unit: 4 n-blocks x TFC token fragments over k-steps [kb0, kb1).
-template <int TFC, int TFMAX, int KSPLIT, int FIRST, bool FOLD>
+template <int TFC, int TFMAX, int KSPLIT, int FIRST, bool FOLD, int GW = 4>
 __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const int32_t* __restrict__ rowmap,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
@@ -176,15 +180,15 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const int K, const int kb0, const int kb1, f32x4* red,
                                             const int rows_total, const bool act_kmajor,
                                             const float* __restrict__ bias, const FoldOut& fold) {
-    constexpr int PF = StreamPF<TFC>::value;
+    constexpr int PF = GW == 4 ? StreamPF<TFC>::value : MOE_PF_NARROW;
     constexpr int NGB = 4 / KSPLIT;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, g = lane >> 4;
     const int ks = wave % KSPLIT, ngs = wave / KSPLIT;
     const int nblk = N >> 4, kblk = K >> 5;
-    f32x4 acc[4][TFC];
+    f32x4 acc[GW][TFC];
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf)
+    for (int nf = 0; nf < GW; ++nf)
 #pragma unroll
         for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -192,10 +196,10 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     float fw[TFC];
     fold_rows<TFC, FOLD>(fold, tl, ftok, fw);
     if (active && kb0 < kb1) {
-        const uint16_t* wp[4];
+        const uint16_t* wp[GW];
 #pragma unroll
-        for (int nf = 0; nf < 4; ++nf) {
-            const int nb = min(ng * 4 + nf, nblk - 1);
+        for (int nf = 0; nf < GW; ++nf) {
+            const int nb = min(ng * GW + nf, nblk - 1);
             wp[nf] = wpk + (static_cast<size_t>(tl.expert) * nblk + nb) * kblk * 512 + lane * 8;
         }
         const bool km = FIRST == 0 ? true : act_kmajor;     // the second product always reads h
@@ -208,10 +212,10 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
             ap[tf] = km ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
         }
         const size_t kstride = km ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
-        bf16x8 a[PF][4], b[PF][TFC];
+        bf16x8 a[PF][GW], b[PF][TFC];
         auto issue = [&](int slot, int kb) {
 #pragma unroll
-            for (int nf = 0; nf < 4; ++nf)
+            for (int nf = 0; nf < GW; ++nf)
                 a[slot][nf] = *reinterpret_cast<const bf16x8*>(wp[nf] + static_cast<size_t>(kb) * 512);
 #pragma unroll
             for (int tf = 0; tf < TFC; ++tf) b[slot][tf] = *reinterpret_cast<const bf16x8*>(ap[tf] + kb * kstride);
@@ -220,7 +224,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 #pragma unroll
             for (int tf = 0; tf < TFC; ++tf)
 #pragma unroll
-                for (int nf = 0; nf < 4; ++nf)
+                for (int nf = 0; nf < GW; ++nf)
                     acc[nf][tf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[slot][nf], b[slot][tf], acc[nf][tf], 0, 0, 0);
         };
         // prologue: always PF steps of loads (past the end the last step is re-read, never used)
@@ -249,9 +253,9 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
 
     if (KSPLIT > 1) {
         if (active && ks > 0) {
-            f32x4* dst = red + (static_cast<size_t>((ks - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+            f32x4* dst = red + (static_cast<size_t>((ks - 1) * NGB + ngs) * GW * TFMAX) * 64 + lane;
 #pragma unroll
-            for (int nf = 0; nf < 4; ++nf)
+            for (int nf = 0; nf < GW; ++nf)
 #pragma unroll
                 for (int tf = 0; tf < TFC; ++tf) dst[(nf * TFMAX + tf) * 64] = acc[nf][tf];
         }
@@ -261,9 +265,9 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
         if (active && ks == 0) {
 #pragma unroll
             for (int s = 1; s < KSPLIT; ++s) {
-                const f32x4* src = red + (static_cast<size_t>((s - 1) * NGB + ngs) * 4 * TFMAX) * 64 + lane;
+                const f32x4* src = red + (static_cast<size_t>((s - 1) * NGB + ngs) * GW * TFMAX) * 64 + lane;
 #pragma unroll
-                for (int nf = 0; nf < 4; ++nf)
+                for (int nf = 0; nf < GW; ++nf)
 #pragma unroll
                     for (int tf = 0; tf < TFC; ++tf) acc[nf][tf] += src[(nf * TFMAX + tf) * 64];
             }
@@ -271,7 +275,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     }
     if (active && ks == 0) {
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        store_group<TFC, FIRST, FOLD>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
+        store_group<TFC, FIRST, FOLD, GW>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
     }
     if (KSPLIT > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // `red` may be reused
 }
@@ -492,6 +496,38 @@ int device_cu_count() {
     return cus[dev];
 }
 
+// Second product of a layer of at most 16 tokens when its experts are so few that groups of 64 columns leave
+// most CUs without a unit (one decoder token with two experts: 64 units): a unit is one 16-column block, the
+// four wavefronts of a block split the contraction as usual and keep 16 KiB-steps of weights in flight each.
+__global__ __launch_bounds__(256) void ffn_stream_narrow_kernel(const uint16_t* __restrict__ act,
+                                                                const uint16_t* __restrict__ wpk,
+                                                                void* __restrict__ outp,
+                                                                const Tile* __restrict__ tiles,
+                                                                const int32_t* __restrict__ ntiles_p, int N, int K,
+                                                                int rows_total, const float* __restrict__ bias) {
+    __shared__ f32x4 red[3 * 64];
+    const int ks = threadIdx.x >> 6;
+    const int nblk = N >> 4, kblk = K >> 5;
+    const int kb_per = (kblk + 3) / 4;
+    const int kb0 = min(kblk, ks * kb_per), kb1 = min(kblk, kb0 + kb_per);
+    const int nbu = ntiles_p[0] * nblk;
+    // as in ffn_stream_kernel: every block that runs gets the same number of units, and the blocks of an XCD
+    // take consecutive units
+    int stride = gridDim.x;
+    const int rounds = (nbu + stride - 1) / stride;
+    if (rounds > 0) stride = (nbu + rounds - 1) / rounds;
+    if (static_cast<int>(blockIdx.x) >= stride) return;
+    const int pb = (stride % 8 == 0) ? static_cast<int>(blockIdx.x & 7) * (stride >> 3) + static_cast<int>(blockIdx.x >> 3)
+                                     : static_cast<int>(blockIdx.x);
+    const FoldOut none{nullptr, nullptr, nullptr};
+    for (int base = 0; base < nbu; base += stride) {
+        const int bu = base + pb;
+        if (bu >= nbu) break;                             // block-uniform
+        stream_unit<1, 1, 4, 0, false, 1>(act, nullptr, wpk, outp, tiles[bu / nblk], bu % nblk, true, N, K, kb0, kb1, red,
+                                          rows_total, true, bias, none);
+    }
+}
+
 template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
@@ -681,6 +717,17 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
+    // few tokens and few experts: units of one column block, so that every CU has one
+    const bool narrow = ffn_tfmax(s) == 1 && ks2 == 4 && fold.out == nullptr && pt == nullptr &&
+                        tiles_expected * ((d / 16 + 3) / 4) < device_cu_count();
+    if (narrow) {
+        long grid = max_tiles * (d / 16);
+        if (grid > device_cu_count()) grid = device_cu_count();
+        hipLaunchKernelGGL(ffn_stream_narrow_kernel, dim3(static_cast<unsigned>(grid < 1 ? 1 : grid)), dim3(256), 0, st, h, p2,
+                           static_cast<void*>(y_perm), tiles, ntiles, d, f, A, b2);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+        return mark(4, st);
+    }
     switch (ffn_tfmax(s)) {
         case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
         case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
