@@ -167,6 +167,26 @@ def main() -> int:
         f"{int(counts.max())}; {copies} weight copies rotated "
         f"({copies * 2 * w_bytes_one / 1e9:.2f} GB of distinct weights between reuses)")
 
+    edges = [0, 1, 8, 64, 312, 1 << 30]                  # 312: about the rows at which an expert turns MFMA-bound
+    bins = [int(((counts >= lo) & (counts < hi)).sum()) for lo, hi in zip(edges[:-1], edges[1:])]
+    top = np.sort(counts)[::-1]
+    Hshow = cfg.H if cfg.H is not None else max(1, cfg.E // 8)
+    log(f"[bench] tokens per expert: 0: {bins[0]} experts, 1-7: {bins[1]}, 8-63: {bins[2]}, 64-311: {bins[3]}, "
+        f">=312: {bins[4]}; top-{Hshow} experts hold {100.0 * top[:Hshow].sum() / max(1, counts.sum()):.1f} % of the assignments")
+    # context, not a target: a large device-to-device copy on the same device, same run
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(4):
+        cp_dst.copy_(cp_src)
+    c1.record()
+    torch.cuda.synchronize()
+    log(f"[bench] context: device-to-device copy of 1 GiB: {4 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9:.0f} GB/s "
+        f"read + written")
+    del cp_src, cp_dst
+
     # ---- pass A: the timed steps -----------------------------------------------------------------
     for i in range(W):
         L.forward(H=H, copy=i)

@@ -117,6 +117,20 @@ size_t moe_parameter_movement_bytes(const moe_shape* shape);
 size_t moe_activation_movement_bytes(const moe_shape* shape);
 
 /*
+ * Load balancing over several expert-holding devices (Section 3.3, last paragraph: the expert workloads,
+ * sorted by compute intensity, are dealt out round-robin).  Host arithmetic, no GPU, HOST pointers.
+ *   counts [E]   tokens per expert (all experts have the same shape, so compute intensity orders like the
+ *                token count); skip [E] or NULL: experts with skip[e] != 0 take no part (e.g. the hot set that
+ *                stays on the main device).
+ *   device_of [E] out: experts with counts[e] > 0 that are not skipped, ordered by count descending (equal
+ *                counts by lowest index), get devices 0, 1, ..., n_devices-1, 0, 1, ... in that order; every
+ *                other expert gets -1.
+ * MOE_ERR_INVALID_ARG on a NULL counts / device_of, n_devices < 1 or a negative count; nothing is written then.
+ */
+moe_status moe_plan_devices(int32_t E, const int32_t* counts, const uint8_t* skip, int32_t n_devices,
+                            int32_t* device_of);
+
+/*
  * Parameter movement on demand (Section 3.2, Section 4.1: only activated experts are brought in): copies the
  * packed weights (`which` = 1: W1, 2: W2) of the experts with fetch_mask[e] != 0 from a HOST buffer holding all
  * E experts' packed weights (layout of moe_pack_weights; pinned memory for an asynchronous copy) to the same

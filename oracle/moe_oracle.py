@@ -167,6 +167,21 @@ def hot_expert_count(counts, alpha, bw_a, bw_b):
     return max(0, min(int(np.floor(h + 0.5)), E))
 
 
+def plan_devices(counts, n_devices, skip=None):
+    """Load balancing over several expert-holding devices (Section 3.3, last paragraph): the experts
+    that have tokens (and are not in `skip`, e.g. the hot set kept on the main device), sorted by
+    compute intensity -- the token count, all experts having the same shape -- are dealt out
+    round-robin.  Equal counts keep their index order.  Returns device_of[E], -1 for experts that take
+    no part."""
+    counts = np.asarray(counts)
+    device_of = np.full(counts.shape[0], -1, dtype=np.int64)
+    taking_part = [e for e in range(counts.shape[0]) if counts[e] > 0 and (skip is None or not skip[e])]
+    by_load = sorted(taking_part, key=lambda e: (-int(counts[e]), e))
+    for position, e in enumerate(by_load):
+        device_of[e] = position % n_devices
+    return device_of
+
+
 def parameter_movement(E, d_model, d_ff):
     """Number of expert parameters of one MoE layer, i.e. what moving every expert to the compute
     device moves (Section 3.2, Eq. 1): two matrices of d_model x d_ff per expert."""

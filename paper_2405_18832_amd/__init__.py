@@ -22,7 +22,7 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 
 EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
-           "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_fetch_experts",
+           "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts",
            "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_biased", "moe_combine",
            "moe_layer_forward", "moe_layer_forward_biased"]
 
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.moe_parameter_movement_bytes.restype = sz
     lib.moe_activation_movement_bytes.argtypes = [sp]
     lib.moe_activation_movement_bytes.restype = sz
+    lib.moe_plan_devices.argtypes = [i32, vp, vp, i32, vp]
+    lib.moe_plan_devices.restype = ctypes.c_int
     lib.moe_fetch_experts.argtypes = [sp, i32, vp, vp, vp, vp]
     lib.moe_fetch_experts.restype = ctypes.c_int
     lib.moe_select_hot.argtypes = [sp, vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, vp, vp, vp]
@@ -169,6 +171,18 @@ def moe_parameter_movement_bytes(shape) -> int:
 
 def moe_activation_movement_bytes(shape) -> int:
     return int(load().moe_activation_movement_bytes(ctypes.byref(shape)))
+
+
+def moe_plan_devices(counts, skip, n_devices: int):
+    """counts, skip: host int32 / uint8 arrays (numpy or CPU tensors; skip may be None).  Returns a numpy int32
+    array device_of[E]."""
+    import numpy as np
+    c = np.ascontiguousarray(np.asarray(counts), dtype=np.int32)
+    k = None if skip is None else np.ascontiguousarray(np.asarray(skip), dtype=np.uint8)
+    out = np.empty(c.shape[0], dtype=np.int32)
+    _check(load().moe_plan_devices(int(c.shape[0]), c.ctypes.data, None if k is None else k.ctypes.data,
+                                   int(n_devices), out.ctypes.data), "moe_plan_devices")
+    return out
 
 
 def moe_fetch_experts(shape, which, src_host, fetch_mask_host, dst_device, stream=None) -> None:

@@ -99,6 +99,31 @@ size_t moe_activation_movement_bytes(const moe_shape* shape) {
     return static_cast<size_t>(2) * shape->T * shape->d_model * elem_size(shape->dtype);
 }
 
+moe_status moe_plan_devices(int32_t E, const int32_t* counts, const uint8_t* skip, int32_t n_devices,
+                            int32_t* device_of) {
+    if (counts == nullptr || device_of == nullptr || n_devices < 1 || E < 1 || E > MOE_MAX_E) return MOE_ERR_INVALID_ARG;
+    for (int e = 0; e < E; ++e)
+        if (counts[e] < 0) return MOE_ERR_INVALID_ARG;
+    int order[MOE_MAX_E];
+    int n = 0;
+    for (int e = 0; e < E; ++e) {
+        device_of[e] = -1;
+        if (counts[e] > 0 && (skip == nullptr || skip[e] == 0)) order[n++] = e;
+    }
+    // insertion sort, stable: count descending, equal counts stay in index order
+    for (int i = 1; i < n; ++i) {
+        const int e = order[i];
+        int j = i;
+        while (j > 0 && counts[order[j - 1]] < counts[e]) {
+            order[j] = order[j - 1];
+            --j;
+        }
+        order[j] = e;
+    }
+    for (int i = 0; i < n; ++i) device_of[order[i]] = i % n_devices;
+    return MOE_OK;
+}
+
 moe_status moe_fetch_experts(const moe_shape* shape, int32_t which, const void* src_host,
                              const uint8_t* fetch_mask_host, void* dst_device, void* stream) {
     moe_status st = check_shape(shape);

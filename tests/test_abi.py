@@ -117,6 +117,28 @@ def test_data_movement_calculators():
     assert lib.moe_fetch_experts(ctypes.byref(s), 1, FAKE, None, FAKE, None) == moe.MOE_ERR_INVALID_ARG
 
 
+def test_plan_devices_against_oracle():
+    # host arithmetic of the library against the oracle's round-robin placement (Section 3.3, last paragraph)
+    import numpy as np
+    from oracle import moe_oracle as orc
+    rng = np.random.default_rng(5)
+    for E, G in [(1, 1), (8, 2), (64, 3), (128, 4), (128, 7), (1024, 8)]:
+        counts = rng.integers(0, 6, size=E) * rng.integers(0, 40, size=E)        # zeros and ties on purpose
+        skip = (rng.random(E) < 0.2).astype(np.uint8)
+        for sk in (None, skip):
+            got = moe.moe_plan_devices(counts, sk, G)
+            assert np.array_equal(got, orc.plan_devices(counts, G, sk))
+    lib = moe.load()
+    c = np.array([1, 2, 3], dtype=np.int32)
+    out = np.full(3, 77, dtype=np.int32)
+    assert lib.moe_plan_devices(3, c.ctypes.data, None, 0, out.ctypes.data) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_plan_devices(3, None, None, 2, out.ctypes.data) == moe.MOE_ERR_INVALID_ARG
+    assert lib.moe_plan_devices(3, c.ctypes.data, None, 2, None) == moe.MOE_ERR_INVALID_ARG
+    bad = np.array([1, -2, 3], dtype=np.int32)
+    assert lib.moe_plan_devices(3, bad.ctypes.data, None, 2, out.ctypes.data) == moe.MOE_ERR_INVALID_ARG
+    assert np.all(out == 77)                                                       # nothing written on error
+
+
 def test_binding_raises_on_error():
     with pytest.raises(moe.MoEError) as ei:
         moe.moe_combine(shape(), FAKE, FAKE, FAKE, FAKE, None, None, stream=0)

@@ -358,3 +358,31 @@ def test_h_rounding_mode_is_close_to_exact():
     err = orc.rel_error(yb, y)
     assert 1e-4 < err.max() < 1e-2
     assert np.sqrt(np.mean((yb - y) ** 2)) / np.sqrt(np.mean(y ** 2)) < 3e-3
+
+
+def test_plan_devices_round_robin_by_load():
+    """Section 3.3, last paragraph: expert workloads sorted by compute intensity are dealt out round-robin.
+    A hand-worked case, and what the rule guarantees: device sizes differ by at most one expert, the device
+    loads are ordered like the device numbers, and no device carries more than the lightest one plus the
+    largest single expert."""
+    #            e:  0   1   2   3   4   5   6   7
+    counts = np.array([5, 0, 9, 5, 1, 7, 0, 3])
+    # by load: e2(9) e5(7) e0(5) e3(5) e7(3) e4(1); ties (e0, e3) by index; on 3 devices: 0 1 2 0 1 2
+    assert orc.plan_devices(counts, 3).tolist() == [2, -1, 0, 0, 2, 1, -1, 1]
+    # the hot set stays where it is: skip e2 and e5 -> e0 e3 e7 e4 on 2 devices: 0 1 0 1
+    skip = np.array([0, 0, 1, 0, 0, 1, 0, 0])
+    assert orc.plan_devices(counts, 2, skip).tolist() == [0, -1, -1, 1, 1, -1, -1, 0]
+    rng = np.random.default_rng(7)
+    for E, G in [(16, 2), (128, 4), (128, 5), (64, 64), (10, 16)]:
+        c = (rng.zipf(1.3, size=E) % 500) * (rng.random(E) < 0.8)
+        dev = orc.plan_devices(c, G)
+        active = c > 0
+        assert np.all(dev[~active] == -1) and np.all((dev[active] >= 0) & (dev[active] < G))
+        sizes = np.array([(dev == g).sum() for g in range(G)])
+        loads = np.array([c[dev == g].sum() for g in range(G)])
+        assert sizes.max() - sizes.min() <= 1 and np.all(np.diff(sizes) <= 0)
+        assert np.all(np.diff(loads) <= 0)                       # device 0 gets the heaviest of every round
+        assert loads.max() - loads.min() <= c.max()
+        # every round hands out non-increasing counts
+        order = sorted(np.flatnonzero(active), key=lambda e: (-c[e], e))
+        assert [dev[e] for e in order] == [i % G for i in range(len(order))]
