@@ -96,6 +96,31 @@ EXTRA = {
 }
 
 
+def _random_configs(n):
+    """Seeded random shapes: ragged token counts, expert counts on both sides of the kernels' internal limits
+    (16, 64, 128, 256 experts; 16 / 64 / 128 rows per expert), every k, both activations, with and without
+    biases, skewed and flat routing."""
+    rng = np.random.default_rng(20240607)
+    out = {}
+    for i in range(n):
+        E = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64, 100, 130, 257]))
+        k = int(min(E, rng.choice([1, 1, 2, 2, 3, 4, 8])))
+        f32 = i % 6 == 5
+        d = int(rng.choice([32, 64, 96] if f32 else [32, 64, 96, 160, 256, 512]))
+        f = int(rng.choice([32, 64, 128] if f32 else [32, 64, 128, 224, 512, 1024]))
+        T = int(rng.choice([1, 7, 16, 17, 63, 129, 300] if f32 else [1, 7, 16, 17, 63, 129, 300, 777, 1500]))
+        name = f"rand_{i}"
+        out[name] = wl.MoEConfig(name, T=T, d_model=d, d_ff=f, E=E, k=k, dtype="f32" if f32 else "bf16",
+                                 renormalize=bool(rng.integers(0, 2)), seed=100 + i,
+                                 zipf_s=float(rng.choice([0.0, 1.0, 3.0])) or None, gate_std=float(rng.choice([0.02, 0.3, 1.0])),
+                                 activation=str(rng.choice(["relu", "gelu"])), expert_bias=bool(rng.integers(0, 2)))
+    return out
+
+
+RANDOM = _random_configs(12)
+EXTRA.update(RANDOM)
+
+
 def CFG(name):
     if name in wl.CONFIGS:
         return wl.CONFIGS[name]
@@ -104,7 +129,7 @@ def CFG(name):
 
 SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", "k_equals_E",
          "many_experts", "experts_200", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
-         "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"]
+         "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"] + list(RANDOM)
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128",
           "tokens_8k", "tokens_12k_top1"]
 LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4"]
