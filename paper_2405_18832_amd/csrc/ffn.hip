@@ -307,6 +307,13 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
     int ftok[TFC];
     float fw[TFC];
     fold_rows<TFC, FOLD>(fold, tl, ftok, fw);
+    // the token rows behind the lane's permuted positions: fetched before the barrier, whose wait hides them
+    int rows_of[TFC];
+#pragma unroll
+    for (int tf = 0; tf < TFC; ++tf) {
+        rows_of[tf] = tl.row0 + min(tf * 16 + r, tl.rows - 1);
+        if (rowmap != nullptr) rows_of[tf] = rowmap[rows_of[tf]];
+    }
     // every wavefront has finished reading the previous unit's rows
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // rows -> LDS: wavefront w copies the fragments (tf, kb) with kb = w, w + 4, ...; a lane fetches the
@@ -315,8 +322,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
     const uint32_t lds0 = lds_address(tok_lds);
 #pragma unroll
     for (int tf = 0; tf < TFC; ++tf) {
-        int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
-        if (rowmap != nullptr) row = rowmap[row];
+        const int row = rows_of[tf];
         const uint16_t* ap =
             act_kmajor ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
         for (int kb = wave; kb < kblk; kb += 4) copy16_to_lds(ap + kb * kstride, lds0 + (tf * kblk + kb) * 1024);
