@@ -66,13 +66,13 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "dd0cc8047dc3873b", "ffn_tile.hip": "d6e05b7ff0696246",
+TRAFFIC_SOURCES = {"ffn.hip": "70eaa5058c3cc82c", "ffn_tile.hip": "d6e05b7ff0696246",
                    "tile_schedule.hpp": "cfb38ed553932c2c", "common.hpp": "0cbda28b4f9aeb0c"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316516090, ("switch_base", "stream_w2"): 320291603,
-    ("nllb_decode", "stream_w1"): 1643649609, ("nllb_decode", "stream_w2"): 1645602205,
-    ("nllb_prefill_skew", "stream_w1"): 1158813280, ("nllb_prefill_skew", "stream_w2"): 1152626714,
-    ("nllb_prefill_skew", "tile_w1"): 2484292575, ("nllb_prefill_skew", "tile_w2"): 2208258704,
+    ("switch_base", "stream_w1"): 316497081, ("switch_base", "stream_w2"): 320284080,
+    ("nllb_decode", "stream_w1"): 1643650027, ("nllb_decode", "stream_w2"): 1645598399,
+    ("nllb_prefill_skew", "stream_w1"): 1158824483, ("nllb_prefill_skew", "stream_w2"): 1152634078,
+    ("nllb_prefill_skew", "tile_w1"): 2489611011, ("nllb_prefill_skew", "tile_w2"): 2211052202,
 }
 
 
