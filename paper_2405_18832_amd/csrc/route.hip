@@ -287,7 +287,6 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
                       margin ? margin + (live ? t : 0) : nullptr, hist);
     }
     __syncthreads();
-    const int nchunks = gridDim.x;
     for (int e = threadIdx.x; e < E; e += NT) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
 }
 
@@ -596,7 +595,6 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     topk_from_lds(L + tl * Ep, E, k, renorm, sub, live, topk_idx + o, topk_w + o,
                   margin ? margin + (live ? t : 0) : nullptr, hist);
     __syncthreads();
-    const int nchunks = gridDim.x;
     for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
 }
 
