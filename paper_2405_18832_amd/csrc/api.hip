@@ -237,18 +237,13 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
     const TileLists lists = ffn_tile_lists(*shape, at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big),
                                            at<int32_t>(ws, L.ntiles), at<float>(ws, L.partials));
     hipError_t e;
-    int nchunks = 0;
     const int tok = route_chunk_tokens(*shape);
-    if (shape->T > 0) {
-        nchunks = (shape->T + tok - 1) / tok;
-        e = launch_route_fused(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, at<float>(ws, L.gate_part), hs);
-        if (e != hipSuccess) return MOE_ERR_HIP;
-    }
     // few assignments: the finalize block also places them (one launch less)
     const bool fused_place = shape->T > 0 && scan_can_place(*shape);
     const PlaceArgs place{idx, perm, inv, tokmap, shape->T * shape->k, shape->k, tok * shape->k};
-    e = launch_scan_finalize(hist, nchunks, shape->E, cnt, offsets, derive ? H : -1, derive ? own_mask : nullptr,
-                             mask, &lists, fused_place ? &place : nullptr, hs);
+    e = launch_route_finalize(*shape, x, w_gate, gate_bias, idx, gate, nullptr, hist, at<float>(ws, L.gate_part), cnt,
+                              offsets, derive ? H : -1, derive ? own_mask : nullptr, mask, &lists,
+                              fused_place ? &place : nullptr, hs);
     if (e != hipSuccess) return MOE_ERR_HIP;
     if (hot_mask_out != nullptr) {
         e = launch_mask_out(used, hot_mask_out, shape->E, hs);

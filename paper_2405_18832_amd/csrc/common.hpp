@@ -304,6 +304,10 @@ struct PlaceArgs {
     int A, k, chunk;
 };
 bool scan_can_place(const moe_shape& s);
+hipError_t launch_route_finalize(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                                 int32_t* idx, float* gate, float* margin, int32_t* hist_ws, float* gate_part_ws,
+                                 int32_t* counts, int32_t* offsets, int H, uint8_t* hot_mask, const uint8_t* mask_in,
+                                 const TileLists* lists, const PlaceArgs* place, hipStream_t st);
 hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t* counts, int32_t* offsets, int H,
                                 uint8_t* hot_mask, const uint8_t* mask_in, const TileLists* lists,
                                 const PlaceArgs* place, hipStream_t st);

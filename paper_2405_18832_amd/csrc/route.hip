@@ -302,13 +302,12 @@ __global__ __launch_bounds__(NW * 64) void route_fused_kernel(const ST* __restri
 constexpr int kScanPlaceMaxE = 256;     // largest E and ...
 constexpr long kScanPlaceMaxA = 512;    // ... most assignments for which the finalize block also places
 
-__global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
-                                                             int E, int32_t* __restrict__ counts,
-                                                             int32_t* __restrict__ offsets, int H,
-                                                             uint8_t* __restrict__ hot_mask,
-                                                             const uint8_t* __restrict__ mask_in,
-                                                             const TileLists lists, const int want_tiles,
-                                                             const PlaceArgs place) {
+// the work of scan_finalize_kernel, by a block of 1024 threads
+__device__ __forceinline__ void scan_finalize_body(int32_t* __restrict__ chunk_hist, int nchunks, int E,
+                                                   int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                   int H, uint8_t* __restrict__ hot_mask,
+                                                   const uint8_t* __restrict__ mask_in, const TileLists lists,
+                                                   const int want_tiles, const PlaceArgs place) {
     __shared__ int32_t cnt[MOE_MAX_E];
     __shared__ int32_t scan[MOE_MAX_E];
     __shared__ int32_t place_next[16][kScanPlaceMaxE];   // per wavefront: next free slot of every expert
@@ -404,6 +403,16 @@ __global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict
                     place.chunk, c);
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+__global__ __launch_bounds__(1024) void scan_finalize_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
+                                                             int E, int32_t* __restrict__ counts,
+                                                             int32_t* __restrict__ offsets, int H,
+                                                             uint8_t* __restrict__ hot_mask,
+                                                             const uint8_t* __restrict__ mask_in,
+                                                             const TileLists lists, const int want_tiles,
+                                                             const PlaceArgs place) {
+    scan_finalize_body(chunk_hist, nchunks, E, counts, offsets, H, hot_mask, mask_in, lists, want_tiles, place);
 }
 
 // Hot-set size from the counts (Section 3.3, Eq. 6) and the top-H mask.  One block, thread e owns
@@ -598,6 +607,70 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
     for (int e = threadIdx.x; e < E; e += 256) chunk_hist[static_cast<size_t>(blockIdx.x) * E + e] = hist[e];
 }
 
+// route_topk_kernel and scan_finalize_kernel in one block of 1024 threads, for layers of at most 64 tokens and
+// 256 experts (decoder steps): the 16 wavefronts take 4 tokens each, the four 16-token chunks keep their
+// histograms in LDS, and the block goes straight on to the prefix sums, tile lists and (small layers) the
+// placement.  One launch and one trip through memory less on a path that is a chain of short kernels.
+// Dynamic LDS: logits [64][E + 1] floats, then histograms [4][E] ints.
+constexpr int kTopkFinalizeMaxE = 256;
+__global__ __launch_bounds__(1024) void route_topk_finalize_kernel(const float* __restrict__ part,
+                                                                   const float* __restrict__ bias,
+                                                                   int32_t* __restrict__ topk_idx,
+                                                                   float* __restrict__ topk_w,
+                                                                   float* __restrict__ margin,
+                                                                   int32_t* __restrict__ chunk_hist, int T, int E, int k,
+                                                                   int renorm, int Tpad, int32_t* __restrict__ counts,
+                                                                   int32_t* __restrict__ offsets, int H,
+                                                                   uint8_t* __restrict__ hot_mask,
+                                                                   const uint8_t* __restrict__ mask_in,
+                                                                   const TileLists lists, const int want_tiles,
+                                                                   const PlaceArgs place) {
+    extern __shared__ float lds[];
+    const int Ep = E + 1;
+    float* L = lds;
+    int32_t* hist = reinterpret_cast<int32_t*>(lds + 64 * Ep);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nchunks = Tpad >> 4;                         // <= 4
+    for (int i = threadIdx.x; i < 4 * E; i += 1024) hist[i] = 0;
+    // 4 logits per thread and pass, their 4 * kGateSplit partial sums loaded before any is added
+    for (int i0 = threadIdx.x; i0 < Tpad * E; i0 += 4 * 1024) {
+        float p[4][kGateSplit];
+        float b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + u * 1024, Tpad * E - 1);   // past the end: re-read, not stored
+            const int tl = i / E, e = i - tl * E;
+            b[u] = bias ? bias[e] : 0.f;
+#pragma unroll
+            for (int ks = 0; ks < kGateSplit; ++ks) p[u][ks] = part[(static_cast<size_t>(ks) * Tpad + tl) * E + e];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * 1024;
+            if (i >= Tpad * E) break;
+            const int tl = i / E, e = i - tl * E;
+            float sum = b[u];
+#pragma unroll
+            for (int ks = 0; ks < kGateSplit; ++ks) sum += p[u][ks];      // fixed order
+            L[tl * Ep + e] = sum;
+        }
+    }
+    __syncthreads();
+    const int grp = lane >> 4, sub = lane & 15;
+    const int tl = wave * 4 + grp;                         // 16 wavefronts x 4 tokens
+    if (wave * 4 < Tpad) {                                 // wave-uniform: Tpad is a multiple of 16
+        const bool live = tl < T;
+        const size_t o = static_cast<size_t>(live ? tl : 0) * k;
+        topk_from_lds(L + tl * Ep, E, k, renorm, sub, live, topk_idx + o, topk_w + o,
+                      margin ? margin + (live ? tl : 0) : nullptr, hist + (tl >> 4) * E);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nchunks * E; i += 1024) chunk_hist[i] = hist[i];     // [chunk][E], as the other kernels
+    __threadfence_block();
+    __syncthreads();
+    scan_finalize_body(chunk_hist, nchunks, E, counts, offsets, H, hot_mask, mask_in, lists, want_tiles, place);
+}
+
 static hipError_t launch_route_small(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                                      int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* part,
                                      hipStream_t st) {
@@ -648,18 +721,47 @@ hipError_t launch_scan_finalize(int32_t* chunk_hist, int nchunks, int E, int32_t
     return hipGetLastError();
 }
 
-hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
-                        int32_t* idx, float* gate, float* margin, int32_t* counts,
-                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws, float* gate_part_ws,
-                        hipStream_t st) {
+// routing followed by the finalize step; one kernel does both for decoder-sized layers
+hipError_t launch_route_finalize(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                                 int32_t* idx, float* gate, float* margin, int32_t* hist_ws, float* gate_part_ws,
+                                 int32_t* counts, int32_t* offsets, int H, uint8_t* hot_mask, const uint8_t* mask_in,
+                                 const TileLists* lists, const PlaceArgs* place, hipStream_t st) {
     int nchunks = 0;
     if (s.T > 0) {
         const int tok = route_chunk_tokens(s);
         nchunks = (s.T + tok - 1) / tok;
+        if (route_is_split(s) && gate_part_ws != nullptr && s.E <= kTopkFinalizeMaxE) {
+            const int tfs = (s.T + 15) / 16, Tpad = tfs * 16, nbs = (s.E + 15) / 16;
+            hipLaunchKernelGGL(gate_partial_kernel, dim3(nbs, kGateSplit, tfs), dim3(64), 0, st,
+                               static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w_gate), gate_part_ws, s.T,
+                               s.d_model, s.E, Tpad);
+            hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return err;
+            const size_t lds = static_cast<size_t>(64) * (s.E + 1) * 4 + static_cast<size_t>(4) * s.E * 4;
+            if (lds > 32 * 1024) {     // with the finalize step's static arrays: above the default per-block limit
+                err = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_finalize_kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+                if (err != hipSuccess) return err;
+            }
+            const TileLists none{nullptr, nullptr, nullptr, nullptr, 16, 0};
+            const PlaceArgs no_place{nullptr, nullptr, nullptr, nullptr, 0, 1, 1};
+            hipLaunchKernelGGL(route_topk_finalize_kernel, dim3(1), dim3(1024), lds, st, gate_part_ws, bias, idx, gate,
+                               margin, hist_ws, s.T, s.E, s.k, s.renormalize, Tpad, counts, offsets, H, hot_mask, mask_in,
+                               lists ? *lists : none, lists ? 1 : 0, place ? *place : no_place);
+            return hipGetLastError();
+        }
         hipError_t err = launch_route_fused(s, x, w_gate, bias, idx, gate, margin, hist_ws, gate_part_ws, st);
         if (err != hipSuccess) return err;
     }
-    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, nullptr, nullptr, nullptr, st);
+    return launch_scan_finalize(hist_ws, nchunks, s.E, counts, offsets, H, hot_mask, mask_in, lists, place, st);
+}
+
+hipError_t launch_route(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
+                        int32_t* idx, float* gate, float* margin, int32_t* counts,
+                        int32_t* offsets, int32_t H, uint8_t* hot_mask, int32_t* hist_ws, float* gate_part_ws,
+                        hipStream_t st) {
+    return launch_route_finalize(s, x, w_gate, bias, idx, gate, margin, hist_ws, gate_part_ws, counts, offsets, H, hot_mask,
+                                 nullptr, nullptr, nullptr, st);
 }
 
 }  // namespace moe
