@@ -738,10 +738,13 @@ hipError_t launch_route_finalize(const moe_shape& s, const void* x, const void* 
             hipError_t err = hipGetLastError();
             if (err != hipSuccess) return err;
             const size_t lds = static_cast<size_t>(64) * (s.E + 1) * 4 + static_cast<size_t>(4) * s.E * 4;
-            if (lds > 32 * 1024) {     // with the finalize step's static arrays: above the default per-block limit
+            static size_t lds_allowed = 32 * 1024;   // with the finalize step's static arrays, more would be above the
+            if (lds > lds_allowed) {                 // default per-block limit: raise it once to the largest case
+                constexpr size_t most = static_cast<size_t>(64) * (kTopkFinalizeMaxE + 1) * 4 + 4 * kTopkFinalizeMaxE * 4;
                 err = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_finalize_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(most));
                 if (err != hipSuccess) return err;
+                lds_allowed = most;
             }
             const TileLists none{nullptr, nullptr, nullptr, nullptr, 16, 0};
             const PlaceArgs no_place{nullptr, nullptr, nullptr, nullptr, 0, 1, 1};
