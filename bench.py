@@ -6,11 +6,17 @@ combine) over one batch of a synthetic layer; inputs and weights are resident in
 timed region.  Prints ONE JSON line with tokens/s, the roofline figures of the dominant kernel
 (measured with HIP events recorded on the launch stream), and the CPU oracle timed on the host
 cores on a bounded sample of the same workload.
+
+The headline workload is the largest preset that fits one GPU: the NLLB-MoE-shaped encoder prefill
+layer (Table 2 shapes, skewed expert load as in Fig. 3).  A default run (no --workload) then measures
+the other presets and the hot-only shares of the two skewed presets in the same process and reports
+them under the key "configs" of the same JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import ctypes
+import gc
 import json
 import os
 import sys
@@ -26,6 +32,11 @@ import workloads as wl
 
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
+
+HEADLINE = "nllb_prefill_skew"
+# what a default run measures after the headline: (workload, share)
+OTHERS = [("nllb_prefill_skew", "hot"), ("nllb_decode", "full"), ("switch_large_skew", "full"),
+          ("switch_large_skew", "hot"), ("switch_base", "full"), ("tiny_f32", "full")]
 
 
 def log(*a):
@@ -76,8 +87,10 @@ TRAFFIC_BYTES = {
 }
 
 
-def recorded_traffic(workload: str, tag: str):
+def recorded_traffic(workload: str, share: str, tag: str):
     import hashlib
+    if share != "full":
+        return None
     for fn, want in TRAFFIC_SOURCES.items():
         path = os.path.join(ROOT, "paper_2405_18832_amd", "csrc", fn)
         try:
@@ -94,40 +107,24 @@ def describe(cfg) -> str:
             + (f", gate bias ln Zipf(s={cfg.zipf_s})" if cfg.zipf_s else ""))
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="switch_base",
-                    choices=wl.CONFIG_ORDER + [n + "_matched" for n in ("switch_large_skew", "nllb_prefill_skew")]
-                    + list(wl.EXTRA_CONFIGS))
-    ap.add_argument("--share", default="full", choices=["full", "hot"],
-                    help="full layer, or only the top-H hot experts' share (workloads with a hot mask)")
-    ap.add_argument("--copies", type=int, default=0,
-                    help="weight copies rotated through the timing loop (0 = enough for 2 GB between reuses)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--measure-fetch", action="store_true",
-                    help="also time moe_fetch_experts (activated experts' W1 from pinned host memory) and log the rate")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        return 2
+def config_of(name: str):
+    return (wl.matched_noise(wl.CONFIGS[name[:-8]]) if name.endswith("_matched")
+            else wl.CONFIGS.get(name) or wl.EXTRA_CONFIGS[name])
 
+
+def measure(name: str, share: str, K: int, W: int, copies_arg: int = 0, cpu_baseline: bool = False,
+            measure_fetch: bool = False, breakdown: bool = True) -> dict:
+    """One workload: W warm-up steps, exactly K timed steps, then the same K steps again with HIP events
+    around every expert-FFN kernel.  Returns the fields of the JSON line that depend on the workload."""
     import torch
 
     import paper_2405_18832_amd as moe
     from paper_2405_18832_amd.device_layer import DeviceLayer
 
-    moe.load()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    name = args.workload
-    cfg = (wl.matched_noise(wl.CONFIGS[name[:-8]]) if name.endswith("_matched")
-           else wl.CONFIGS.get(name) or wl.EXTRA_CONFIGS[name])
-    K, W = args.steps, args.warmup
+    cfg = config_of(name)
     es = 2 if cfg.dtype == "bf16" else 4
-    log(f"[bench] workload {describe(cfg)}")
+    log(f"[bench] workload {describe(cfg)}, share {share}")
 
     # ---- inputs into HBM --------------------------------------------------------------------
     x = wl.make_activations(cfg)
@@ -148,10 +145,9 @@ def main() -> int:
         L.upload_experts(expert, active, workers=16)
     log(f"[bench] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s")
 
-    hot = args.share == "hot"
+    hot = share == "hot"
     if hot and cfg.H is None:
-        log("[bench] this workload defines no hot mask; use --share full")
-        return 2
+        raise SystemExit("[bench] this workload defines no hot mask; use --share full")
     H = cfg.H if hot else -1
     L.forward(H=H, debug=True)
     torch.cuda.synchronize()
@@ -161,7 +157,7 @@ def main() -> int:
     n_active = int(ran.sum())
     A_run = int(counts[ran].sum())
     w_bytes_one = n_active * cfg.d_model * cfg.d_ff * es            # one product's weights
-    copies = args.copies or max(1, min(16, int(np.ceil(2e9 / max(1, 2 * w_bytes_one)))))
+    copies = copies_arg or max(1, min(16, int(np.ceil(2e9 / max(1, 2 * w_bytes_one)))))
     L.make_copies(copies)
     log(f"[bench] experts run {n_active}/{cfg.E}, assignments run {A_run}/{cfg.A}, max tokens/expert "
         f"{int(counts.max())}; {copies} weight copies rotated "
@@ -173,19 +169,6 @@ def main() -> int:
     Hshow = cfg.H if cfg.H is not None else max(1, cfg.E // 8)
     log(f"[bench] tokens per expert: 0: {bins[0]} experts, 1-7: {bins[1]}, 8-63: {bins[2]}, 64-311: {bins[3]}, "
         f">=312: {bins[4]}; top-{Hshow} experts hold {100.0 * top[:Hshow].sum() / max(1, counts.sum()):.1f} % of the assignments")
-    # context, not a target: a large device-to-device copy on the same device, same run
-    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cp_dst = torch.empty_like(cp_src)
-    cp_dst.copy_(cp_src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(4):
-        cp_dst.copy_(cp_src)
-    c1.record()
-    torch.cuda.synchronize()
-    log(f"[bench] context: device-to-device copy of 1 GiB: {4 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9:.0f} GB/s "
-        f"read + written")
-    del cp_src, cp_dst
 
     # ---- pass A: the timed steps -----------------------------------------------------------------
     for i in range(W):
@@ -234,21 +217,24 @@ def main() -> int:
         torch.cuda.synchronize()
         return a.elapsed_time(z) / reps * 1e3
 
-    mask_t = L.hot_mask.clone() if hot else None
-    L.route(H=H)
-    br = {"route_us": timed(lambda i: L.route(H=H)),
-          "permute_us": timed(lambda i: L.permute()),
-          "expert_ffn_us": timed(lambda i: L.expert_ffn(mask=mask_t, copy=i)),
-          "combine_us": timed(lambda i: L.combine(mask=mask_t))}
+    br = {}
+    if breakdown:
+        mask_t = L.hot_mask.clone() if hot else None
+        L.route(H=H)
+        reps = 50 if ms_step < 1.0 else 10
+        br = {"route_us": timed(lambda i: L.route(H=H), reps),
+              "permute_us": timed(lambda i: L.permute(), reps),
+              "expert_ffn_us": timed(lambda i: L.expert_ffn(mask=mask_t, copy=i), reps),
+              "combine_us": timed(lambda i: L.combine(mask=mask_t), reps)}
 
     # ---- roofline of the dominant kernel ---------------------------------------------------------
     # Experts with >= 128 rows run in the LDS-tiled kernel, the others in the weight-streaming kernel
     # (only when the layer has >= 128 tokens, else everything streams).
     d, f = cfg.d_model, cfg.d_ff
     big = ran & (counts >= 128) if (cfg.dtype == "bf16" and cfg.T >= 128) else np.zeros_like(ran)
-    small = ran & ~big
-    rows_s, rows_b = int(counts[small].sum()), int(counts[big].sum())
-    wb_s, wb_b = int(small.sum()) * d * f * es, int(big.sum()) * d * f * es
+    smalls = ran & ~big
+    rows_s, rows_b = int(counts[smalls].sum()), int(counts[big].sum())
+    wb_s, wb_b = int(smalls.sum()) * d * f * es, int(big.sum()) * d * f * es
     names = ["ffn_tile_kernel (x.W1 product, large experts)", "ffn_stream_kernel (x.W1 product, small experts)",
              "ffn_tile_kernel (h.W2 product, large experts)", "ffn_stream_kernel (h.W2 product, small experts)"]
     tags = ["tile_w1", "stream_w1", "tile_w2", "stream_w2"]
@@ -261,17 +247,19 @@ def main() -> int:
     kd = max(kern, key=lambda q: q["us"])
     t_flop = kd["flops"] / (PEAK_BF16_TFLOPS * 1e12)
     t_byte = kd["bytes"] / (PEAK_HBM_GBPS * 1e9)
-    traffic = recorded_traffic(name, kd["tag"])
-    if cfg.dtype != "bf16":
+    traffic = recorded_traffic(name, share, kd["tag"])
+    if cfg.dtype != "bf16" or kd["us"] <= 0:
         roof = None
     elif t_flop > t_byte:
         ach = kd["flops"] / (kd["us"] * 1e-6) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic}
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
+                "frac_between_events": kd["flops"] / (kd["us_raw"] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS}
     else:
         ach = kd["bytes"] / (kd["us"] * 1e-6) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBPS, "traffic": traffic}
+                "frac": ach / PEAK_HBM_GBPS, "traffic": traffic,
+                "frac_between_events": kd["bytes"] / (kd["us_raw"] * 1e-6) / 1e9 / PEAK_HBM_GBPS}
     if roof is not None:
         roof.update(kernel=kd["name"], kernel_us=kd["us"], kernel_us_min=kd["us_min"],
                     kernel_us_between_events=kd["us_raw"], empty_event_interval_us=ev_gap,
@@ -280,13 +268,17 @@ def main() -> int:
 
     layer_flops = 2.0 * cfg.T * d * cfg.E + 4.0 * A_run * d * f
     layer_bytes = 2 * w_bytes_one + 2 * cfg.T * d * es + d * cfg.E * es
+    t_floor = max(layer_flops / (PEAK_BF16_TFLOPS * 1e12), layer_bytes / (PEAK_HBM_GBPS * 1e9))
     layer = {"tflops": layer_flops / (ms_step * 1e-3) / 1e12,
              "useful_GBps": layer_bytes / (ms_step * 1e-3) / 1e9,
              "useful_bytes": layer_bytes, "flops": layer_flops,
+             # whole step against the larger of its two floors (all flops at the MFMA peak, all useful bytes at
+             # the HBM peak)
+             "frac_of_roofline": t_floor / (ms_step * 1e-3) if cfg.dtype == "bf16" else None,
              "experts_run": n_active, "assignments_run": A_run, **{k_: round(v, 2) for k_, v in br.items()}}
 
     # ---- optional: parameter movement on demand over the host link (Section 3.2), logged only ----------
-    if args.measure_fetch and cfg.dtype == "bf16":
+    if measure_fetch and cfg.dtype == "bf16":
         fetch_mask = torch.from_numpy(ran.astype(np.uint8))
         host_w1 = L.w1.cpu().pin_memory()
         dst = torch.empty_like(L.w1)
@@ -306,7 +298,7 @@ def main() -> int:
 
     # ---- CPU oracle on a bounded sample of the same workload -------------------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         from oracle import moe_oracle as orc
         try:
             from threadpoolctl import threadpool_info
@@ -322,24 +314,103 @@ def main() -> int:
         reps, cdt = 0, 0.0
         while reps == 0 or (cdt < 10.0 and reps < 200):      # about 10 s of CPU work
             t0 = time.perf_counter()
-            ref = orc.layer_forward(xs, wg, b, expert, cfg.k, cfg.renormalize, mask_np,
-                                    return_intermediates=True, h_dtype="bf16" if cfg.dtype == "bf16" else None)
+            ref = orc.layer_forward(xs, wg, b, expert, cfg.k, cfg.renormalize, mask_np, return_intermediates=True)
             cdt += time.perf_counter() - t0
             reps += 1
         ok = ref["margin"] >= 1e-4
         got = L.out[:S].float().cpu().numpy()
-        err = float(orc.rel_error(got[ok], ref["out"][ok]).max()) if ok.any() else 0.0
+        # the timed oracle never rounds the hidden activation; the second figure is against the oracle that
+        # rounds it to the storage type once, as a run in that type does
+        err_rows = orc.rel_error_rows(got[ok], ref["out"][ok])
+        err = float(err_rows.max()) if ok.any() else 0.0
+        vec = float(orc.row_error_norms(got[ok], ref["out"][ok]).max()) if ok.any() else 0.0
+        err_s = None
+        if cfg.dtype == "bf16":
+            ref_s = orc.layer_forward(xs, wg, b, expert, cfg.k, cfg.renormalize, mask_np, h_dtype="bf16")
+            err_s = float(orc.rel_error_rows(got[ok], ref_s[ok]).max()) if ok.any() else 0.0
         cpu = {"value": S * reps / cdt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
                "sample": f"first {S} of {cfg.T} tokens, whole layer, fp64 numpy, {reps} repetitions in {cdt:.2f} s "
                          f"(host cores visible: {len(os.sched_getaffinity(0))})",
-               "gpu_vs_oracle_max_rel_err": err}
-        log(f"[bench] oracle: {S} tokens x {reps} in {cdt:.2f} s on {threads} threads; GPU vs oracle max rel err {err:.3e}")
+               "gpu_vs_oracle_max_rel_err": err, "gpu_vs_oracle_max_row_l2_err": vec,
+               "gpu_vs_storage_precision_oracle_max_rel_err": err_s}
+        log(f"[bench] oracle: {S} tokens x {reps} in {cdt:.2f} s on {threads} threads; GPU vs oracle: element-wise "
+            f"max rel err {err:.3e} (per-row normalised), worst row L2 err {vec:.3e}; vs the oracle that stores the "
+            f"hidden activation in bf16: {err_s if err_s is None else format(err_s, '.3e')}")
 
-    out = {"metric": "MoE-FFN tokens/s", "value": tokens_s, "unit": "tokens/s", "n_gpus": 1, "steps": K,
-           "warmup": W, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-           "config": {"workload": describe(cfg), "share": args.share, "weight_copies_rotated": copies},
+    res = {"value": tokens_s, "ms_per_step": ms_step, "dtype": cfg.dtype,
+           "config": {"workload": describe(cfg), "share": share, "weight_copies_rotated": copies},
            "roofline": roof, "cpu_baseline": cpu, "layer": layer}
+    del L, cache
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None,
+                    choices=wl.CONFIG_ORDER + [n + "_matched" for n in ("switch_large_skew", "nllb_prefill_skew")]
+                    + list(wl.EXTRA_CONFIGS),
+                    help=f"measure this workload only (default: {HEADLINE}, then the other presets under 'configs')")
+    ap.add_argument("--share", default="full", choices=["full", "hot"],
+                    help="full layer, or only the top-H hot experts' share (workloads with a hot mask)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="weight copies rotated through the timing loop (0 = enough for 2 GB between reuses)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--measure-fetch", action="store_true",
+                    help="also time moe_fetch_experts (activated experts' W1 from pinned host memory) and log the rate")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2405_18832_amd as moe
+
+    moe.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    K, W = args.steps, args.warmup
+    name = args.workload or HEADLINE
+
+    # context, not a target: a large device-to-device copy on the same device, same run
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(4):
+        cp_dst.copy_(cp_src)
+    c1.record()
+    torch.cuda.synchronize()
+    log(f"[bench] context: device-to-device copy of 1 GiB: {4 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9:.0f} GB/s "
+        f"read + written")
+    del cp_src, cp_dst
+    torch.cuda.empty_cache()
+
+    head = measure(name, args.share, K, W, args.copies, cpu_baseline=not args.no_cpu_baseline,
+                   measure_fetch=args.measure_fetch)
+    out = {"metric": "MoE-FFN tokens/s", "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": K,
+           "warmup": W, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic", "config": head["config"],
+           "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"], "layer": head["layer"]}
+
+    if args.workload is None:
+        # the other presets and the hot-only shares: short steps, so more of them for a steady figure
+        configs = {f"{name}:{args.share}": {"ms_per_step": head["ms_per_step"], "tokens_s": head["value"],
+                                            "roofline": head["roofline"],
+                                            "frac_of_roofline": head["layer"]["frac_of_roofline"]}}
+        for oname, oshare in OTHERS:
+            r = measure(oname, oshare, max(K, 50), max(W, 10), 0, cpu_baseline=False, breakdown=False)
+            configs[f"{oname}:{oshare}"] = {"ms_per_step": r["ms_per_step"], "tokens_s": r["value"],
+                                            "steps": max(K, 50), "roofline": r["roofline"],
+                                            "frac_of_roofline": r["layer"]["frac_of_roofline"],
+                                            "experts_run": r["layer"]["experts_run"],
+                                            "assignments_run": r["layer"]["assignments_run"]}
+        out["configs"] = configs
     print(json.dumps(out), flush=True)
     return 0
 

@@ -22,7 +22,12 @@
  *    asynchronous on it; they never synchronise and never copy to the host.  Token
  *    counts stay on the device: kernels read them there.
  *  - Arguments are validated on the host before anything is launched; on an error
- *    nothing is written.  Errors are return codes only.
+ *    nothing is written (one exception, stated there: moe_fetch_experts).  Errors are
+ *    return codes only.
+ *  - Every entry point works on the calling thread's current HIP device.  The first call on a
+ *    device (or moe_init) sets the kernels up for it once, under a lock; after that, calls from
+ *    several host threads and on several devices are independent, except where a call says
+ *    otherwise (moe_set_profile_events).
  *  - Row-major everywhere, last index contiguous.  dtype selects the storage type
  *    of x, w_gate, W1, W2, x_perm and out; products are accumulated in fp32.
  *    Gate weights, logits margins and y_perm are always fp32; indices are int32.
@@ -63,6 +68,15 @@ typedef struct {
 
 #define MOE_MAX_K 8
 #define MOE_MAX_E 1024
+
+/*
+ * One-time set-up for the current device: raises the kernels' dynamic-LDS limits and asks the runtime for
+ * their occupancy.  Optional -- every entry point that launches kernels does the same on its first call on a
+ * device -- but a caller that records its first call into a HIP graph should call it before the capture
+ * starts, so that none of these runtime calls happens while the stream is capturing.  Thread-safe; repeated
+ * calls return at once.  MOE_ERR_HIP if the runtime refuses.
+ */
+moe_status moe_init(void);
 
 /* Human-readable name of a status code (host pointer to a static string). */
 const char* moe_status_string(moe_status s);
@@ -136,7 +150,10 @@ moe_status moe_plan_devices(int32_t E, const int32_t* counts, const uint8_t* ski
  * E experts' packed weights (layout of moe_pack_weights; pinned memory for an asynchronous copy) to the same
  * offsets of a DEVICE buffer of the same size, one copy per expert on `stream`; other experts' device memory
  * is left as it is.  fetch_mask is a HOST array [E] -- the caller has brought counts or a hot mask over, that
- * being the one host round trip the scheme needs.  Returns after enqueueing; MOE_ERR_HIP if a copy fails.
+ * being the one host round trip the scheme needs.  Returns after enqueueing.  Arguments are validated before
+ * the first copy; if the runtime then refuses a copy the call returns MOE_ERR_HIP at once, and the copies of
+ * the experts before that one stay enqueued (the only case in this library where an error leaves a partial
+ * effect: treat the destination's contents as undefined).
  */
 moe_status moe_fetch_experts(const moe_shape* shape, int32_t which, const void* src_host,
                              const uint8_t* fetch_mask_host, void* dst_device, void* stream);
@@ -211,7 +228,8 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
  *   [0] before the first product (x.W1^T, ReLU) of the large experts' tiled kernel (if launched),
  *   [1] after it, [2] after the first product of the small experts' weight-streaming kernel,
  *   [3] after the second product (h.W2^T) of the tiled kernel, [4] after that of the streaming kernel.
- * The handles are copied; the array need not outlive the call.  Process-global, not thread-safe.
+ * The handles are copied; the array need not outlive the call.  Process-global (all devices, all threads) and
+ * not thread-safe: set it only while no other thread is inside an expert-FFN call.
  */
 void moe_set_profile_events(void* const* events);
 

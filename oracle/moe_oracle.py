@@ -334,3 +334,31 @@ def rel_error(got, ref):
     rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
     den = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
     return np.abs(got - ref) / den
+
+
+def rel_error_rows(got, ref):
+    """Element-wise |got-ref| / max(|ref|, rms of the element's own row of ref), for 2-D arrays
+    [rows, d].  Token rows of an MoE layer differ in scale (the gate weight multiplies the whole
+    row), so the floor that keeps the relative error meaningful near zero is taken per row; a row
+    of zeros (a token none of whose experts ran) gets the floor 1, i.e. its absolute error."""
+    ref = np.asarray(ref, F64)
+    got = np.asarray(got, F64)
+    out = np.empty(ref.shape, F64)
+    for i in range(ref.shape[0]):
+        rms = float(np.sqrt(np.mean(ref[i] * ref[i]))) if ref.shape[1] else 0.0
+        floor = rms if rms > 0 else 1.0
+        out[i] = np.abs(got[i] - ref[i]) / np.maximum(np.abs(ref[i]), floor)
+    return out
+
+
+def row_error_norms(got, ref):
+    """Per row ||got-ref||_2 / ||ref||_2 (the relative error of the row as a vector); a row of
+    zeros in ref reports ||got||_2, its absolute error."""
+    ref = np.asarray(ref, F64)
+    got = np.asarray(got, F64)
+    out = np.empty(ref.shape[0], F64)
+    for i in range(ref.shape[0]):
+        num = float(np.sqrt(np.sum((got[i] - ref[i]) ** 2)))
+        den = float(np.sqrt(np.sum(ref[i] ** 2)))
+        out[i] = num / den if den > 0 else num
+    return out

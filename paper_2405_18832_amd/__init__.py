@@ -20,7 +20,8 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP
 MOE_F32, MOE_BF16 = 0, 1
 MOE_MAX_K, MOE_MAX_E = 8, 1024
 
-EXPORTS = ["moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
+EXPORTS = ["moe_init",
+           "moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
            "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts",
            "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_biased", "moe_combine",
@@ -56,6 +57,8 @@ def load() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     sp = ctypes.POINTER(moe_shape)
+    lib.moe_init.restype = ctypes.c_int
+    lib.moe_init.argtypes = []
     lib.moe_status_string.restype = ctypes.c_char_p
     lib.moe_status_string.argtypes = [ctypes.c_int]
     lib.moe_workspace_bytes.restype = sz
@@ -134,6 +137,10 @@ def _stream(stream) -> Optional[int]:
 def _check(status: int, where: str) -> None:
     if status != MOE_OK:
         raise MoEError(status, where)
+
+
+def moe_init() -> None:
+    _check(load().moe_init(), "moe_init")
 
 
 def moe_workspace_bytes(shape: moe_shape) -> int:

@@ -1,12 +1,17 @@
 // C ABI of the MoE FFN library: argument validation on the host, then asynchronous kernel
 // launches on the caller's stream.  No entry point allocates, synchronises or copies to the host.
+#include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "common.hpp"
 
 using namespace moe;
 
 namespace {
+
+std::mutex g_setup_mutex;
+std::atomic<bool> g_device_ready[kMaxDevices];
 
 moe_status check_shape(const moe_shape* s) {
     if (s == nullptr) return MOE_ERR_INVALID_ARG;
@@ -37,7 +42,34 @@ template <typename T> inline T* at(void* ws, size_t off) {
 
 }  // namespace
 
+namespace moe {
+
+int current_device_index() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    return dev;
+}
+
+hipError_t ensure_ready() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_device_ready[dev].load(std::memory_order_acquire)) return hipSuccess;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (g_device_ready[dev].load(std::memory_order_acquire)) return hipSuccess;
+    if ((e = configure_ffn_kernels(dev)) != hipSuccess) return e;
+    if ((e = configure_tile_kernels(dev)) != hipSuccess) return e;
+    if ((e = configure_route_kernels(dev)) != hipSuccess) return e;
+    g_device_ready[dev].store(true, std::memory_order_release);
+    return hipSuccess;
+}
+
+}  // namespace moe
+
 extern "C" {
+
+moe_status moe_init(void) { return from_hip(ensure_ready()); }
 
 const char* moe_status_string(moe_status s) {
     switch (s) {
@@ -68,6 +100,7 @@ moe_status moe_pack_weights(const moe_shape* shape, int32_t which, const void* s
     moe_status st = check_shape(shape);
     if (st != MOE_OK) return st;
     if ((which != 1 && which != 2) || src == nullptr || dst == nullptr || src == dst) return MOE_ERR_INVALID_ARG;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     return from_hip(launch_pack(*shape, which, src, dst, static_cast<hipStream_t>(stream)));
 }
 
@@ -83,6 +116,7 @@ moe_status moe_route(const moe_shape* shape, const void* x, const void* w_gate, 
         return MOE_ERR_INVALID_ARG;
     st = check_ws(shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_route(*shape, x, w_gate, gate_bias, topk_idx, topk_w, margin, counts, offsets, H,
                                  hot_mask, at<int32_t>(ws, L.hist), at<float>(ws, L.gate_part),
@@ -148,6 +182,7 @@ moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double 
     if (counts == nullptr) return MOE_ERR_INVALID_ARG;
     if (!(alpha >= 0.0) || !(bw_a > 0.0) || !(bw_b >= 0.0) || std::isinf(alpha) || std::isinf(bw_a) || std::isinf(bw_b))
         return MOE_ERR_INVALID_ARG;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     return from_hip(launch_select_hot(shape->E, counts, alpha, bw_a, bw_b, H_out, hot_mask,
                                       static_cast<hipStream_t>(stream)));
 }
@@ -162,6 +197,7 @@ moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* top
     if (x_perm != nullptr && x == nullptr) return MOE_ERR_INVALID_ARG;
     st = check_ws(shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_permute(*shape, x, topk_idx, offsets, perm, inv_perm, x_perm, at<int32_t>(ws, L.hist),
                                    static_cast<hipStream_t>(stream)));
@@ -183,6 +219,7 @@ moe_status moe_expert_ffn_biased(const moe_shape* shape, const void* x_perm, con
         return MOE_ERR_INVALID_ARG;
     st = check_ws(shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     const WsLayout L = ws_layout(*shape);
     return from_hip(launch_expert_ffn(*shape, x_perm, w1, w2, b1, b2, offsets, mask, y_perm, at<void>(ws, L.h),
                                       at<Tile>(ws, L.tiles), at<Tile>(ws, L.tiles_big), at<int32_t>(ws, L.ntiles),
@@ -196,6 +233,7 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
     if (shape->T == 0) return MOE_OK;
     if (y_perm == nullptr || inv_perm == nullptr || topk_idx == nullptr || topk_w == nullptr || out == nullptr)
         return MOE_ERR_INVALID_ARG;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     return from_hip(launch_combine(*shape, y_perm, inv_perm, topk_idx, topk_w, mask, out,
                                    static_cast<hipStream_t>(stream)));
 }
@@ -219,6 +257,7 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
         return MOE_ERR_INVALID_ARG;
     st = check_ws(shape, ws, ws_bytes);
     if (st != MOE_OK) return st;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const WsLayout L = ws_layout(*shape);
     int32_t* idx = topk_idx ? topk_idx : at<int32_t>(ws, L.idx);

@@ -80,15 +80,20 @@ constexpr int kFirstRelu = 1;
 constexpr int kFirstGelu = 2;
 #endif
 
-// Layout of the bf16 intermediate h = relu(x . W1^T) in the workspace: k-step-major, [d_ff / 32][A][32]
-// (A = T * k rows).  The second product consumes h 32 k at a time: the 32 values of consecutive rows
-// are then 64 bytes apart, so a 16-row MFMA operand fragment is one contiguous KiB and a row tile of a
-// k-step a contiguous run of full cache lines (row-major, each row would contribute half a line).
-// Element (row, n) lives at:
+// Layout of the bf16 row operands that the products read 32 k at a time (the intermediate
+// h = act(x . W1^T) and the gathered token rows): blocks of kRowBlock rows, and inside a block k-step-major,
+// [rows / 256][K / 32][256][32].  The 32 values of consecutive rows are 64 bytes apart, so a 16-row MFMA
+// operand fragment is one contiguous KiB (row-major, each row would contribute half a cache line), a row
+// tile of one k-step is at most two contiguous runs, and consecutive k-steps of a row are 16 KiB apart: a
+// block that walks along K reads one linear stream.  (With the k-step outermost over all A rows, [K / 32][A][32],
+// consecutive steps of a 32 k-row layer were 2 MiB apart and the global-to-LDS copies of the tiled kernel ran
+// at two thirds of the rate they reach on a linear stream.)  Element (row, n) of a tensor with `ksteps` = K / 32:
+constexpr int kRowBlock = 256;
 #ifdef __HIPCC__
-__device__ __forceinline__ size_t h_index(int row, int n, int rows_total) {
-    return (static_cast<size_t>(n >> 5) * rows_total + row) * 32 + (n & 31);
+__device__ __forceinline__ size_t h_index(int row, int n, int ksteps) {
+    return ((static_cast<size_t>(row >> 8) * ksteps + (n >> 5)) * kRowBlock + (row & (kRowBlock - 1))) * 32 + (n & 31);
 }
+constexpr int kStepStride = kRowBlock * 32;     // elements between consecutive k-steps of a row
 #endif
 
 #ifdef __HIPCC__
@@ -214,7 +219,7 @@ struct WsLayout {
     size_t ntiles;     // int32 [64]  ([0] = tiles of small experts, [1] = of large experts, [2], [3] counters)
     size_t tiles;      // Tile [A/16 + E + 1]   row tiles of the weight-streaming kernel
     size_t tiles_big;  // Tile [A/256 + E + 1]  row tiles of the LDS-tiled kernel
-    size_t h;          // dtype [A, f]
+    size_t h;          // dtype [A rounded up to kRowBlock, f]
     size_t idx;        // int32 [A]         -- the rest is used by moe_layer_forward only
     size_t gate;       // float [A]
     size_t counts;     // int32 [E]
@@ -225,7 +230,7 @@ struct WsLayout {
     size_t tokmap;     // int32 [A]  token row of each permuted position
     size_t y_perm;     // float [A, d]
     size_t partials;   // float [kSplitSlots, 256, 256]  (only when an expert can reach kBigMinRows rows)
-    size_t x_kmajor;   // bf16 [d/32, A, 32]  gathered token rows, k-step-major (same condition)
+    size_t x_kmajor;   // bf16 [A rounded up to kRowBlock, d]  gathered token rows in the blocked layout (same condition)
     size_t gate_part;  // float [kGateSplit, T rounded up to 16, E]  partial gate logits (layers with route_is_split)
     size_t total;
 };
@@ -256,7 +261,8 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.ntiles = take(64 * 4);
     L.tiles = take((A / 16 + E + 1) * sizeof(Tile));
     L.tiles_big = take((A / 256 + E + 1) * sizeof(Tile));
-    L.h = take(A * s.d_ff * es);
+    const size_t Ab = (A + kRowBlock - 1) / kRowBlock * kRowBlock;     // the blocked layouts hold whole row blocks
+    L.h = take(Ab * s.d_ff * es);
     L.idx = take(A * 4);
     L.gate = take(A * 4);
     L.counts = take(E * 4);
@@ -268,7 +274,7 @@ inline WsLayout ws_layout(const moe_shape& s) {
     L.y_perm = take(A * s.d_model * 4);
     const bool big = s.dtype == MOE_BF16 && s.T >= kBigMinRows;
     L.partials = take(big ? static_cast<size_t>(kSplitSlots) * kBigTileRows * 256 * 4 : 0);
-    L.x_kmajor = take(big ? A * s.d_model * es : 0);
+    L.x_kmajor = take(big ? Ab * s.d_model * es : 0);
     L.gate_part = take(route_is_split(s) ? static_cast<size_t>(kGateSplit) * ((s.T + 15) / 16 * 16) * E * 4 : 0);
     L.total = off;
     return L;
@@ -322,7 +328,7 @@ bool layer_gathers_kmajor(const moe_shape& s);
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st);
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
+                               float* partials, int N, int K, bool act_kmajor, int activation,
                                const float* bias, const FoldOut& fold, hipStream_t st);
 int tile_product_grid();
 hipError_t launch_permute(const moe_shape& s, const void* x, const int32_t* idx,
@@ -343,5 +349,18 @@ void set_profile_events(const hipEvent_t* five_events_or_null);
 
 // number of compute units of the current device (cached)
 int device_cu_count();
+
+// ---- one-time set-up per device ---------------------------------------------------------------
+// Raising a kernel's dynamic-LDS limit and asking for its occupancy are calls into the runtime that do not
+// belong on a launch path (they cost time, and a first call made while a stream is being captured would
+// land inside the capture).  ensure_ready() makes them all, for every kernel of the library, once per
+// device and under a lock; every entry point that launches kernels calls it first.
+constexpr int kMaxDevices = 64;
+constexpr size_t kLdsPerCu = 160 * 1024;
+hipError_t ensure_ready();                       // api.hip
+int current_device_index();                      // api.hip: hipGetDevice clamped to [0, kMaxDevices)
+hipError_t configure_ffn_kernels(int dev);       // ffn.hip
+hipError_t configure_tile_kernels(int dev);      // ffn_tile.hip
+hipError_t configure_route_kernels(int dev);     // route.hip
 
 }  // namespace moe

@@ -6,6 +6,8 @@
 // (Section 2.2), is what shapes the kernel below: it streams every active expert's weights
 // exactly once at full memory bandwidth while the few token rows ride along as the other MFMA
 // operand.
+#include <algorithm>
+
 #include "tile_schedule.hpp"
 
 namespace moe {
@@ -59,11 +61,17 @@ __global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t* __rest
     __shared__ int32_t scan[MOE_MAX_E];
     const int e = threadIdx.x;
     int row0 = 0, m = 0;
-    if (e < E && (mask == nullptr || mask[e] != 0)) {
+    bool bad = false;
+    if (e < E) {
         row0 = offsets[e];
         m = offsets[e + 1] - row0;
-        if (row0 < 0 || m < 0 || row0 + m > A) m = 0;   // offsets that are not prefix sums: run nothing
+        bad = row0 < 0 || m < 0 || row0 + m > A;
+        if (mask != nullptr && mask[e] == 0) m = 0;
     }
+    // Offsets that are not prefix sums (a negative count anywhere, a segment outside [0, A]): run nothing at all.
+    // With every count >= 0 the segments are disjoint and their sum is at most A, which is what the capacity of
+    // the tile lists assumes.
+    if (__syncthreads_or(bad ? 1 : 0)) m = 0;
     emit_tiles(e, row0, m, lists, scan);
 }
 
@@ -137,7 +145,7 @@ __device__ __forceinline__ void fold_rows(const FoldOut& fold, const Tile tl, in
 // Output of one column group (4 n-blocks) x TFC row fragments of a tile, by one whole wavefront.
 template <int TFC, int FIRST, bool FOLD, int GW = 4>
 __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile tl, const int ng, const int nblk,
-                                            const int N, const int rows_total, const float* __restrict__ be,
+                                            const int N, const float* __restrict__ be,
                                             const f32x4 (&acc)[GW][TFC], const FoldOut& fold,
                                             const int (&ftok)[TFC], const float (&fw)[TFC]) {
     static_assert(GW == 4 || (FIRST == 0 && !FOLD), "paired stores need groups of 4 column blocks");
@@ -151,7 +159,7 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
             for (int m = 0; m < 2; ++m) {
                 const int nb = ng * 4 + 2 * m;             // N / 16 is even: the pair exists or not as a whole
                 if (nb >= nblk) continue;                  // wave-uniform
-                store_h_pair<FIRST, true>(outp, tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
+                store_h_pair<FIRST, true>(outp, tl.row0 + lr, ok, nb * 16, N, be, acc[2 * m][tf], acc[2 * m + 1][tf]);
             }
         } else if constexpr (FOLD && GW == 4) {            // the layer output itself
 #pragma unroll
@@ -165,7 +173,7 @@ __device__ __forceinline__ void store_group(void* __restrict__ outp, const Tile 
             for (int nf = 0; nf < GW; ++nf) {
                 const int nb = ng * GW + nf;
                 if (ok && nb < nblk)
-                    store_out<0, true>(outp, tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                    store_out<0, true>(outp, tl.row0 + lr, nb * 16 + g * 4, N, be, acc[nf][tf]);
             }
         }
     }
@@ -178,7 +186,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
                                             const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                             const Tile tl, const int ng, const bool active, const int N,
                                             const int K, const int kb0, const int kb1, f32x4* red,
-                                            const int rows_total, const bool act_kmajor,
+                                            const bool act_kmajor,
                                             const float* __restrict__ bias, const FoldOut& fold) {
     constexpr int PF = GW == 4 ? StreamPF<TFC>::value : MOE_PF_NARROW;
     constexpr int NGB = 4 / KSPLIT;
@@ -209,9 +217,9 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
             int row = tl.row0 + min(tf * 16 + r, tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];       // gather: permuted position -> token row
             // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
-            ap[tf] = km ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
+            ap[tf] = km ? act + h_index(row, g * 8, kblk) : act + static_cast<size_t>(row) * K + g * 8;
         }
-        const size_t kstride = km ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+        const size_t kstride = km ? kStepStride : 32;   // elements per k-step
         bf16x8 a[PF][GW], b[PF][TFC];
         auto issue = [&](int slot, int kb) {
 #pragma unroll
@@ -275,7 +283,7 @@ __device__ __forceinline__ void stream_unit(const uint16_t* __restrict__ act,
     }
     if (active && ks == 0) {
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        store_group<TFC, FIRST, FOLD, GW>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
+        store_group<TFC, FIRST, FOLD, GW>(outp, tl, ng, nblk, N, be, acc, fold, ftok, fw);
     }
     if (KSPLIT > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // `red` may be reused
 }
@@ -291,7 +299,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
                                                 const int32_t* __restrict__ rowmap,
                                                 const uint16_t* __restrict__ wpk, void* __restrict__ outp,
                                                 const Tile tl, const int ng, const bool active, const int N,
-                                                const int K, const int rows_total, const bool act_kmajor,
+                                                const int K, const bool act_kmajor,
                                                 const float* __restrict__ bias, unsigned char* tok_lds,
                                                 const FoldOut& fold) {
     constexpr int PF = MOE_PF_LDS;
@@ -318,13 +326,13 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // rows -> LDS: wavefront w copies the fragments (tf, kb) with kb = w, w + 4, ...; a lane fetches the
     // 16 bytes of its own slot: row (lane % 16), k-group (lane / 16)
-    const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+    const size_t kstride = act_kmajor ? kStepStride : 32;   // elements per k-step
     const uint32_t lds0 = lds_address(tok_lds);
 #pragma unroll
     for (int tf = 0; tf < TFC; ++tf) {
         const int row = rows_of[tf];
         const uint16_t* ap =
-            act_kmajor ? act + h_index(row, g * 8, rows_total) : act + static_cast<size_t>(row) * K + g * 8;
+            act_kmajor ? act + h_index(row, g * 8, kblk) : act + static_cast<size_t>(row) * K + g * 8;
         for (int kb = wave; kb < kblk; kb += 4) copy16_to_lds(ap + kb * kstride, lds0 + (tf * kblk + kb) * 1024);
     }
 
@@ -383,7 +391,7 @@ __device__ __forceinline__ void stream_unit_lds(const uint16_t* __restrict__ act
             if (kb + p < kblk) fma(p, kb + p);
 
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        store_group<TFC, FIRST, FOLD>(outp, tl, ng, nblk, N, rows_total, be, acc, fold, ftok, fw);
+        store_group<TFC, FIRST, FOLD>(outp, tl, ng, nblk, N, be, acc, fold, ftok, fw);
     }
 }
 
@@ -397,12 +405,12 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int K, int balance,
                                                          const Tile* __restrict__ big_tiles,
                                                          const float* __restrict__ partials, int tile_grid,
-                                                         int rows_total, int act_kmajor, int rows_in_lds,
+                                                         int act_kmajor, int rows_in_lds,
                                                          const float* __restrict__ bias, const FoldOut fold) {
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
     // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
     // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, rows_total, bias, fold);
+    if (partials != nullptr) finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, bias, fold);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -437,23 +445,23 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
         if (KSPLIT == 1 && rows_in_lds) {
             const bool km = act_kmajor != 0;
             if (TFMAX >= 4 && tfc == 4)
-                stream_unit_lds<4, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
+                stream_unit_lds<4, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, km, bias, tok_lds, fold);
             else if (TFMAX >= 4 && tfc == 3)
-                stream_unit_lds<3, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
+                stream_unit_lds<3, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, km, bias, tok_lds, fold);
             else if (TFMAX >= 2 && tfc == 2)
-                stream_unit_lds<2, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
+                stream_unit_lds<2, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, km, bias, tok_lds, fold);
             else
-                stream_unit_lds<1, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, rows_total, km, bias, tok_lds, fold);
+                stream_unit_lds<1, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, km, bias, tok_lds, fold);
             continue;
         }
         if (TFMAX >= 4 && tfc == 4)
-            stream_unit<4, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
+            stream_unit<4, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, act_kmajor != 0, bias, fold);
         else if (TFMAX >= 4 && tfc == 3)
-            stream_unit<3, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
+            stream_unit<3, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, act_kmajor != 0, bias, fold);
         else if (TFMAX >= 2 && tfc == 2)
-            stream_unit<2, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
+            stream_unit<2, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, act_kmajor != 0, bias, fold);
         else
-            stream_unit<1, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, rows_total, act_kmajor != 0, bias, fold);
+            stream_unit<1, TFMAX, KSPLIT, FIRST, FOLD>(act, rowmap, wpk, outp, tl, ng, active, N, K, kb0, kb1, red, act_kmajor != 0, bias, fold);
     }
 }
 
@@ -490,17 +498,21 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+// per device, written once by configure_ffn_kernels (under the set-up lock) before any launch reads them
+static int g_cus[kMaxDevices] = {0};
+
 int device_cu_count() {
-    static int cus[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cus[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cus[dev] = n;
-    }
-    return cus[dev];
+    const int n = g_cus[current_device_index()];
+    return n > 0 ? n : 256;
 }
+
+// resident blocks per CU of a weight-streaming kernel without dynamic LDS, per device
+template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
+struct StreamKernelInfo {
+    static int per_cu[kMaxDevices];
+};
+template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
+int StreamKernelInfo<TFMAX, KSPLIT, FIRST, FOLD>::per_cu[kMaxDevices] = {0};
 
 // Second product of a layer of at most 16 tokens when its experts are so few that groups of 64 columns leave
 // most CUs without a unit (one decoder token with two experts: 64 units): a unit is one 16-column block, the
@@ -510,7 +522,7 @@ __global__ __launch_bounds__(256) void ffn_stream_narrow_kernel(const uint16_t* 
                                                                 void* __restrict__ outp,
                                                                 const Tile* __restrict__ tiles,
                                                                 const int32_t* __restrict__ ntiles_p, int N, int K,
-                                                                int rows_total, const float* __restrict__ bias) {
+                                                                const float* __restrict__ bias) {
     __shared__ f32x4 red[3 * 64];
     const int ks = threadIdx.x >> 6;
     const int nblk = N >> 4, kblk = K >> 5;
@@ -530,43 +542,31 @@ __global__ __launch_bounds__(256) void ffn_stream_narrow_kernel(const uint16_t* 
         const int bu = base + pb;
         if (bu >= nbu) break;                             // block-uniform
         stream_unit<1, 1, 4, 0, false, 1>(act, nullptr, wpk, outp, tiles[bu / nblk], bu % nblk, true, N, K, kb0, kb1, red,
-                                          rows_total, true, bias, none);
+                                          true, bias, none);
     }
 }
 
 template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
 static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                                 const Tile* tiles, const int32_t* ntiles, int N, int K, long max_units,
-                                const Tile* big_tiles, const float* partials, int rows_total, bool act_kmajor,
+                                const Tile* big_tiles, const float* partials, bool act_kmajor,
                                 const float* bias, const FoldOut& fold, hipStream_t st) {
     auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST, FOLD>;
-    static int per_cu = 0;
-    if (per_cu == 0) {
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 256, 0) != hipSuccess || n <= 0) n = 1;
-        per_cu = n;
-    }
-    // KSPLIT = 1: the tile's rows (16 * TFMAX x K, bf16) go through LDS when they fit
+    const int per_cu = std::max(1, StreamKernelInfo<TFMAX, KSPLIT, FIRST, FOLD>::per_cu[current_device_index()]);
+    // KSPLIT = 1: the tile's rows (16 * TFMAX x K, bf16) go through LDS when they fit (the kernel's dynamic-LDS
+    // limit was raised by configure_ffn_kernels)
     const size_t row_bytes = static_cast<size_t>(16) * TFMAX * K * 2;
     const bool rows_in_lds = KSPLIT == 1 && row_bytes <= kStreamRowLdsMax;
     const size_t lds = rows_in_lds ? row_bytes : 0;
-    static size_t lds_allowed = 48 * 1024;
-    if (lds > lds_allowed) {
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kStreamRowLdsMax));
-        if (ea != hipSuccess) return ea;
-        lds_allowed = kStreamRowLdsMax;
-    }
+    // resident blocks per CU: what registers allow, and what the row tiles in LDS leave room for
     int blocks_per_cu = per_cu;
-    if (lds > 0 &&
-        (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks_per_cu, kern, 256, lds) != hipSuccess || blocks_per_cu <= 0))
-        blocks_per_cu = 1;
+    if (lds > 0) blocks_per_cu = std::max(1, std::min(per_cu, static_cast<int>(kLdsPerCu / lds)));
     long grid = static_cast<long>(device_cu_count()) * blocks_per_cu;
     if (grid > max_units && partials == nullptr) grid = max_units;   // with partial tiles to add: all blocks
     if (grid < 1) grid = 1;
     // decode-sized tiles (many units per block): balanced grid; larger tiles: every block stays busy
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(256), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(), rows_total,
+                       ntiles, N, K, TFMAX <= 2 ? 1 : 0, big_tiles, partials, tile_product_grid(),
                        act_kmajor ? 1 : 0, rows_in_lds ? 1 : 0, bias, fold);
     return hipGetLastError();
 }
@@ -574,18 +574,18 @@ static hipError_t launch_stream(const uint16_t* act, const int32_t* rowmap, cons
 template <int TFMAX, int FIRST, bool FOLD>
 static hipError_t launch_stream_kf(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                    void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
-                                   long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
+                                   long max_tiles, const Tile* big_tiles, const float* partials,
                                    bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
     const long ngroups = (N / 16 + 3) / 4;
     if (ksplit == 4)
         return launch_stream<TFMAX, 4, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles * ngroups,
-                                                    big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
+                                                    big_tiles, partials, act_kmajor, bias, fold, st);
     if (ksplit == 2)
         return launch_stream<TFMAX, 2, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                                    max_tiles * ((ngroups + 1) / 2), big_tiles, partials, rows_total,
+                                                    max_tiles * ((ngroups + 1) / 2), big_tiles, partials,
                                                     act_kmajor, bias, fold, st);
     return launch_stream<TFMAX, 1, FIRST, FOLD>(act, rowmap, wpk, outp, tiles, ntiles, N, K,
-                                                max_tiles * ((ngroups + 3) / 4), big_tiles, partials, rows_total,
+                                                max_tiles * ((ngroups + 3) / 4), big_tiles, partials,
                                                 act_kmajor, bias, fold, st);
 }
 
@@ -593,15 +593,54 @@ static hipError_t launch_stream_kf(int ksplit, const uint16_t* act, const int32_
 template <int TFMAX, int FIRST>
 static hipError_t launch_stream_k(int ksplit, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                   void* outp, const Tile* tiles, const int32_t* ntiles, int N, int K,
-                                  long max_tiles, const Tile* big_tiles, const float* partials, int rows_total,
+                                  long max_tiles, const Tile* big_tiles, const float* partials,
                                   bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
     if constexpr (FIRST == 0) {
         if (fold.out != nullptr)
             return launch_stream_kf<TFMAX, 0, true>(ksplit, act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles,
-                                                    big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
+                                                    big_tiles, partials, act_kmajor, bias, fold, st);
     }
     return launch_stream_kf<TFMAX, FIRST, false>(ksplit, act, rowmap, wpk, outp, tiles, ntiles, N, K, max_tiles,
-                                                 big_tiles, partials, rows_total, act_kmajor, bias, fold, st);
+                                                 big_tiles, partials, act_kmajor, bias, fold, st);
+}
+
+template <int TFMAX, int KSPLIT, int FIRST, bool FOLD>
+static hipError_t configure_stream(int dev) {
+    auto kern = ffn_stream_kernel<TFMAX, KSPLIT, FIRST, FOLD>;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 256, 0) != hipSuccess || n <= 0) n = 1;
+    StreamKernelInfo<TFMAX, KSPLIT, FIRST, FOLD>::per_cu[dev] = n;
+    if (KSPLIT == 1)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   static_cast<int>(kStreamRowLdsMax));
+    return hipSuccess;
+}
+
+template <int TFMAX, int KSPLIT>
+static hipError_t configure_stream_products(int dev) {
+    hipError_t e;
+    if ((e = configure_stream<TFMAX, KSPLIT, kFirstRelu, false>(dev)) != hipSuccess) return e;
+    if ((e = configure_stream<TFMAX, KSPLIT, kFirstGelu, false>(dev)) != hipSuccess) return e;
+    if ((e = configure_stream<TFMAX, KSPLIT, 0, false>(dev)) != hipSuccess) return e;
+    return configure_stream<TFMAX, KSPLIT, 0, true>(dev);
+}
+
+template <int TFMAX>
+static hipError_t configure_stream_splits(int dev) {
+    hipError_t e;
+    if ((e = configure_stream_products<TFMAX, 1>(dev)) != hipSuccess) return e;
+    if ((e = configure_stream_products<TFMAX, 2>(dev)) != hipSuccess) return e;
+    return configure_stream_products<TFMAX, 4>(dev);
+}
+
+hipError_t configure_ffn_kernels(int dev) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    g_cus[dev] = n;
+    hipError_t e;
+    if ((e = configure_stream_splits<1>(dev)) != hipSuccess) return e;
+    if ((e = configure_stream_splits<2>(dev)) != hipSuccess) return e;
+    return configure_stream_splits<4>(dev);
 }
 
 // Split K (k-steps of 32) over up to 4 wavefronts.  Decode-sized tiles want many short units
@@ -702,24 +741,24 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
     // Per product: the tiled kernel (large experts) first, then the streaming kernel (small experts), which
     // also adds up the partial tiles that the tiled kernel left for the units it cut along K.
     if (big) {
-        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, A, act_kmajor, s.activation, b1,
+        err = launch_tile_product(true, xp, rowmap, p1, h, bt, ntiles + 1, part1, lists.partials, f, d, act_kmajor, s.activation, b1,
                                   FoldOut{nullptr, nullptr, nullptr}, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(1, st)) != hipSuccess) return err;
     const bool gelu = s.activation == MOE_ACT_GELU;
     switch (ffn_tfmax(s) * 2 + (gelu ? 1 : 0)) {
-        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
-        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
-        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
-        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
-        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
-        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, A, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 2: err = launch_stream_k<1, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 3: err = launch_stream_k<1, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 4: err = launch_stream_k<2, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 5: err = launch_stream_k<2, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        case 8: err = launch_stream_k<4, kFirstRelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
+        default: err = launch_stream_k<4, kFirstGelu>(ks1, xp, rowmap, p1, h, tiles, ntiles, f, d, max_tiles, bt, pt, act_kmajor, b1, FoldOut{nullptr, nullptr, nullptr}, st); break;
     }
     if (err != hipSuccess) return err;
     if ((err = mark(2, st)) != hipSuccess) return err;
     if (big) {
-        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, A, true, s.activation, b2, fold, st);
+        err = launch_tile_product(false, h, nullptr, p2, y_perm, bt, ntiles + 1, part2, lists.partials, d, f, true, s.activation, b2, fold, st);
         if (err != hipSuccess) return err;
     }
     if ((err = mark(3, st)) != hipSuccess) return err;
@@ -730,14 +769,14 @@ hipError_t launch_expert_products(const moe_shape& s, const void* act, const int
         long grid = max_tiles * (d / 16);
         if (grid > device_cu_count()) grid = device_cu_count();
         hipLaunchKernelGGL(ffn_stream_narrow_kernel, dim3(static_cast<unsigned>(grid < 1 ? 1 : grid)), dim3(256), 0, st, h, p2,
-                           static_cast<void*>(y_perm), tiles, ntiles, d, f, A, b2);
+                           static_cast<void*>(y_perm), tiles, ntiles, d, f, b2);
         if ((err = hipGetLastError()) != hipSuccess) return err;
         return mark(4, st);
     }
     switch (ffn_tfmax(s)) {
-        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
-        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
-        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, A, true, b2, fold, st); break;
+        case 1: err = launch_stream_k<1, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, true, b2, fold, st); break;
+        case 2: err = launch_stream_k<2, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, true, b2, fold, st); break;
+        default: err = launch_stream_k<4, 0>(ks2, h, nullptr, p2, y_perm, tiles, ntiles, d, f, max_tiles, bt, pt, true, b2, fold, st); break;
     }
     if (err != hipSuccess) return err;
     return mark(4, st);

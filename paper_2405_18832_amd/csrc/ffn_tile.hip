@@ -73,7 +73,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ ntiles_p,
                                                        int32_t* __restrict__ part_counter,
                                                        float* __restrict__ partials, int N, int K,
-                                                       int rows_total, int act_kmajor,
+                                                       int act_kmajor,
                                                        const float* __restrict__ bias, const FoldOut fold) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // between units, when no stage is in use, the first word of the ring passes the next part's number on
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
     // bytes that belong at its own slot of the fragment: row (lane % 16), k-group (lane / 16).
     const uint16_t* arow[2];
     const uint16_t* brow[2];
-    const size_t kstride = act_kmajor ? static_cast<size_t>(rows_total) * 32 : 32;   // elements per k-step
+    const size_t kstride = act_kmajor ? kStepStride : 32;   // elements per k-step
     auto copy_piece = [&](int st, int q) {             // q = 0 ... 3: row fragment 0, weight 0, row 1, weight 1
         const int i = q >> 1;
         if ((q & 1) == 0) {
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             int row = w.tl.row0 + min((2 * wave + i) * 16 + r, w.tl.rows - 1);
             if (rowmap != nullptr) row = rowmap[row];
             // operand rows are row-major (the caller's x or x_perm) or k-step-major (h, gathered x)
-            arow[i] = act_kmajor ? act + h_index(row, w.kb0 * 32 + g * 8, rows_total)
+            arow[i] = act_kmajor ? act + h_index(row, w.kb0 * 32 + g * 8, kblk)
                                  : act + static_cast<size_t>(row) * K + static_cast<size_t>(w.kb0) * 32 + g * 8;
             const int nb = min(w.nt * 16 + 2 * wave + i, nblk - 1);
             brow[i] = wpk + ((static_cast<size_t>(w.tl.expert) * nblk + nb) * kblk + w.kb0) * 512 + lane * 8;
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                     for (int m = 0; m < 2; ++m) {
                         const int nb = cur.nt * 16 + wn * 4 + 2 * m;   // N / 16 is even: a pair exists as a whole
                         if (nb >= nblk) continue;                       // wave-uniform
-                        store_h_pair<FIRST, false>(outp, cur.tl.row0 + lr, ok, nb * 16, rows_total, be, acc[2 * m][tf],
+                        store_h_pair<FIRST, false>(outp, cur.tl.row0 + lr, ok, nb * 16, N, be, acc[2 * m][tf],
                                                    acc[2 * m + 1][tf]);
                     }
                 } else {
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                         for (int nf = 0; nf < 4; ++nf) {
                             const int nb = cur.nt * 16 + wn * 4 + nf;
                             if (ok && nb < nblk)
-                                store_out<0>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, rows_total, be, acc[nf][tf]);
+                                store_out<0>(outp, cur.tl.row0 + lr, nb * 16 + g * 4, N, be, acc[nf][tf]);
                         }
                     }
                 }
@@ -328,37 +328,43 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 template <int FIRST>
 static hipError_t launch_tile(const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk, void* outp,
                               const Tile* tiles, const int32_t* ntiles, int32_t* part_counter, float* partials, int N,
-                              int K, int rows_total, bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
+                              int K, bool act_kmajor, const float* bias, const FoldOut& fold, hipStream_t st) {
     auto kern = ffn_tile_kernel<FIRST>;
-    constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit
-    static bool configured = false;
-    if (!configured) {
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (ea != hipSuccess) return ea;
-        configured = true;
-    }
+    constexpr int lds = kStages * kStageBytes;  // 128 KiB: above the default per-block limit (raised by configure_tile_kernels)
     // Always the whole chip, one block per CU (the LDS ring allows no more): how many units there are is
     // only known on the device, and few units are cut along K over blocks that would otherwise idle.
     const int grid = tile_product_grid();
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(512), lds, st, act, rowmap, wpk, outp, tiles,
-                       ntiles, part_counter, partials, N, K, rows_total, act_kmajor ? 1 : 0, bias, fold);
+                       ntiles, part_counter, partials, N, K, act_kmajor ? 1 : 0, bias, fold);
     return hipGetLastError();
 }
 
 int tile_product_grid() { return device_cu_count(); }
 
+template <int FIRST>
+static hipError_t configure_tile() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_tile_kernel<FIRST>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kStages * kStageBytes);
+}
+
+hipError_t configure_tile_kernels(int) {
+    hipError_t e;
+    if ((e = configure_tile<0>()) != hipSuccess) return e;
+    if ((e = configure_tile<kFirstRelu>()) != hipSuccess) return e;
+    return configure_tile<kFirstGelu>();
+}
+
 hipError_t launch_tile_product(bool first, const uint16_t* act, const int32_t* rowmap, const uint16_t* wpk,
                                void* outp, const Tile* tiles, const int32_t* ntiles, int32_t* part_counter,
-                               float* partials, int N, int K, int rows_total, bool act_kmajor, int activation,
+                               float* partials, int N, int K, bool act_kmajor, int activation,
                                const float* bias, const FoldOut& fold, hipStream_t st) {
     if (!first)
-        return launch_tile<0>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
+        return launch_tile<0>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K,
                               act_kmajor, bias, fold, st);
     if (activation == MOE_ACT_GELU)
-        return launch_tile<kFirstGelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
+        return launch_tile<kFirstGelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K,
                                        act_kmajor, bias, fold, st);
-    return launch_tile<kFirstRelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K, rows_total,
+    return launch_tile<kFirstRelu>(act, rowmap, wpk, outp, tiles, ntiles, part_counter, partials, N, K,
                                    act_kmajor, bias, fold, st);
 }
 

@@ -71,25 +71,31 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const V* __restrict__ 
     for (int c = lane; c < row_vecs; c += 64) dst[c] = src[c];
 }
 
-// gather into the k-step-major layout of the products' row operand: xk[kb][p][0..31] =
-// x[tokmap[p]][32 kb ... 32 kb + 31] (tokmap may be NULL: identity).  One thread per 16 bytes of the destination, which is written
-// contiguously; every token row is read in 64-byte pieces.
+// gather into the blocked layout of the products' row operand (h_index): element (p, c) of xk is
+// x[tokmap[p]][c] (tokmap may be NULL: identity).  One thread per 16 bytes of the destination, which is written
+// contiguously (the rows past A of the last row block stay unwritten); every token row is read in 64-byte pieces.
 __global__ __launch_bounds__(256) void gather_kmajor_kernel(const uint4* __restrict__ x,
                                                             const int32_t* __restrict__ tokmap,
                                                             uint4* __restrict__ xk, int A, int T, int row_vecs,
                                                             size_t total) {
     const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= total) return;
+    // destination order: [row block][k-step][row in block][4 pieces of 16 bytes]
     const int c = static_cast<int>(i & 3);
-    const size_t pr = i >> 2;                           // kb * A + p
-    const int p = static_cast<int>(pr % A), kb = static_cast<int>(pr / A);
-    const int t = tokmap ? min(max(tokmap[p], 0), T - 1) : p;   // no map: x already has the A rows in order
+    const int r = static_cast<int>((i >> 2) & (kRowBlock - 1));
+    const size_t bk = i >> 10;                          // row block * ksteps + kb
+    const int ksteps = row_vecs >> 2;
+    const int kb = static_cast<int>(bk % ksteps);
+    const size_t p = (bk / ksteps) * kRowBlock + r;
+    if (p >= static_cast<size_t>(A)) return;
+    const int t = tokmap ? min(max(tokmap[p], 0), T - 1) : static_cast<int>(p);   // no map: x already has the A rows in order
     xk[i] = x[static_cast<size_t>(t) * row_vecs + kb * 4 + c];
 }
 
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st) {
     const int A = s.T * s.k;
-    const size_t total = static_cast<size_t>(A) * s.d_model / 8;     // bf16: 8 elements per 16 bytes
+    const size_t Ab = (static_cast<size_t>(A) + kRowBlock - 1) / kRowBlock * kRowBlock;
+    const size_t total = Ab * s.d_model / 8;                          // bf16: 8 elements per 16 bytes
     hipLaunchKernelGGL(gather_kmajor_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
                        static_cast<const uint4*>(x), tokmap, static_cast<uint4*>(xk), A, s.T, s.d_model / 8, total);
     return hipGetLastError();

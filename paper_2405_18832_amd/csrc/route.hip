@@ -486,6 +486,17 @@ static RouteCfg route_cfg(const moe_shape& s) {
 
 int route_chunk_tokens(const moe_shape& s) { return route_cfg(s).tok; }
 
+// Most dynamic LDS a routing kernel asks for: 16 tokens x (1024 experts padded to whole groups of fragments)
+// logits plus the histogram is 78 KiB; 64 tokens x 256 experts is 67 KiB.  configure_route_kernels raises every
+// routing kernel's limit to this once.
+constexpr size_t kRouteLdsMax = 96 * 1024;
+
+template <typename ST, int TF, int NW, int NF>
+static hipError_t configure_route() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(route_fused_kernel<ST, TF, NW, NF>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kRouteLdsMax));
+}
+
 template <typename ST, int TF, int NW, int NF>
 static hipError_t launch_route_inst(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                                     int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, hipStream_t st) {
@@ -493,11 +504,7 @@ static hipError_t launch_route_inst(const moe_shape& s, const void* x, const voi
     const unsigned grid = static_cast<unsigned>((s.T + tok - 1) / tok);
     const size_t lds = static_cast<size_t>(tok) * route_row_stride(s.E, NF) * 4 + static_cast<size_t>(s.E) * 4;
     auto kern = route_fused_kernel<ST, TF, NW, NF>;
-    if (lds > 48 * 1024) {      // more LDS than the default per-block limit: raise it for this kernel
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (ea != hipSuccess) return ea;
-    }
+    if (lds > kRouteLdsMax) return hipErrorInvalidValue;     // cannot happen for E <= MOE_MAX_E (see kRouteLdsMax)
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, st, static_cast<const ST*>(x),
                        static_cast<const ST*>(w_gate), bias, idx, gate, margin, chunk_hist, s.T, s.d_model, s.E, s.k,
                        s.renormalize);
@@ -671,6 +678,33 @@ __global__ __launch_bounds__(1024) void route_topk_finalize_kernel(const float* 
     scan_finalize_body(chunk_hist, nchunks, E, counts, offsets, H, hot_mask, mask_in, lists, want_tiles, place);
 }
 
+constexpr size_t kTopkFinalizeLdsMax = static_cast<size_t>(64) * (kTopkFinalizeMaxE + 1) * 4 + 4 * kTopkFinalizeMaxE * 4;
+
+template <int TF, int NW>
+static hipError_t configure_route_nf() {
+    hipError_t e;
+    if constexpr (NW <= 8) {
+        if ((e = configure_route<uint16_t, TF, NW, 8>()) != hipSuccess) return e;
+    }
+    if ((e = configure_route<uint16_t, TF, NW, 4>()) != hipSuccess) return e;
+    if ((e = configure_route<uint16_t, TF, NW, 2>()) != hipSuccess) return e;
+    return configure_route<uint16_t, TF, NW, 1>();
+}
+
+hipError_t configure_route_kernels(int) {
+    hipError_t e;
+    if ((e = configure_route<float, 1, 4, 1>()) != hipSuccess) return e;
+    if ((e = configure_route_nf<1, 16>()) != hipSuccess) return e;
+    if ((e = configure_route_nf<4, ROUTE_BIG_NW>()) != hipSuccess) return e;
+    if ((e = configure_route_nf<2, ROUTE_T4K_NW>()) != hipSuccess) return e;
+    if ((e = configure_route_nf<1, ROUTE_MID_NW>()) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_kernel),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kRouteLdsMax))) != hipSuccess)
+        return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_finalize_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kTopkFinalizeLdsMax));
+}
+
 static hipError_t launch_route_small(const moe_shape& s, const void* x, const void* w_gate, const float* bias,
                                      int32_t* idx, float* gate, float* margin, int32_t* chunk_hist, float* part,
                                      hipStream_t st) {
@@ -680,12 +714,7 @@ static hipError_t launch_route_small(const moe_shape& s, const void* x, const vo
                        Tpad);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    const size_t lds = static_cast<size_t>(16) * (s.E + 1) * 4 + static_cast<size_t>(s.E) * 4;
-    if (lds > 48 * 1024) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (err != hipSuccess) return err;
-    }
+    const size_t lds = static_cast<size_t>(16) * (s.E + 1) * 4 + static_cast<size_t>(s.E) * 4;   // <= 70 KiB
     hipLaunchKernelGGL(route_topk_kernel, dim3(tfs), dim3(256), lds, st, part, bias, idx, gate, margin, chunk_hist, s.T,
                        s.E, s.k, s.renormalize, Tpad);
     return hipGetLastError();
@@ -737,15 +766,8 @@ hipError_t launch_route_finalize(const moe_shape& s, const void* x, const void* 
                                s.d_model, s.E, Tpad);
             hipError_t err = hipGetLastError();
             if (err != hipSuccess) return err;
+            // at most kTopkFinalizeLdsMax: the limit configure_route_kernels has raised this kernel to
             const size_t lds = static_cast<size_t>(64) * (s.E + 1) * 4 + static_cast<size_t>(4) * s.E * 4;
-            static size_t lds_allowed = 32 * 1024;   // with the finalize step's static arrays, more would be above the
-            if (lds > lds_allowed) {                 // default per-block limit: raise it once to the largest case
-                constexpr size_t most = static_cast<size_t>(64) * (kTopkFinalizeMaxE + 1) * 4 + 4 * kTopkFinalizeMaxE * 4;
-                err = hipFuncSetAttribute(reinterpret_cast<const void*>(route_topk_finalize_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(most));
-                if (err != hipSuccess) return err;
-                lds_allowed = most;
-            }
             const TileLists none{nullptr, nullptr, nullptr, nullptr, 16, 0};
             const PlaceArgs no_place{nullptr, nullptr, nullptr, nullptr, 0, 1, 1};
             hipLaunchKernelGGL(route_topk_finalize_kernel, dim3(1), dim3(1024), lds, st, gate_part_ws, bias, idx, gate,

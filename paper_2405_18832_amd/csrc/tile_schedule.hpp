@@ -56,15 +56,14 @@ __device__ __forceinline__ void unit_of(const TileSchedule& s, int u, int& mt, i
 }
 
 // 4 values of one output row, columns n ... n + 3 (n a multiple of 4).  FIRST != 0 (first product; the value
-// names the activation, kFirstRelu or kFirstGelu): activation, bf16, into the k-step-major h of `rows_total`
-// rows; FIRST == 0 (second product): fp32 into row-major y of N columns.  `bias`: the expert's N bias values
+// names the activation, kFirstRelu or kFirstGelu): activation, bf16, into the blocked h of N columns; FIRST == 0 (second product): fp32 into row-major y of N columns.  `bias`: the expert's N bias values
 // (fp32) or NULL, added before the activation / the store.  STREAMED: the store carries the non-temporal
 // hint, so the rows go to memory while the kernel runs instead of staying behind as dirty L2 lines that the
 // next kernel's weight stream has to push out (the streaming kernel's stores; measured on the Switch-base
 // preset: following product 65 -> 62 us; no effect on the fp32 rows of the second product, which are stored
 // plainly).  The tiled kernel's rows are re-read from L2 and are stored plainly.
 template <int FIRST, bool STREAMED = false>
-__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int rows_total, const float* bias,
+__device__ __forceinline__ void store_out(void* outp, int row, int n, int N, const float* bias,
                                           f32x4 v) {
     if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n);
     if (FIRST) {
@@ -72,7 +71,7 @@ __device__ __forceinline__ void store_out(void* outp, int row, int n, int N, int
         uint2 pk;
         pk.x = pack_bf16x2(z[0], z[1]);
         pk.y = pack_bf16x2(z[2], z[3]);
-        uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total));
+        uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, N >> 5));
         if (STREAMED) {
             __builtin_nontemporal_store(pk.x, q);      // merged into one 8-byte store
             __builtin_nontemporal_store(pk.y, q + 1);
@@ -103,7 +102,7 @@ __device__ __forceinline__ void store_folded(uint16_t* out, int t, float w, int 
 // row: the wavefront's store is one contiguous KiB of h (16 rows x 64 bytes) instead of two stores of
 // 32-byte pieces.  `row_ok`: the lane's row exists (the others take part in the exchange only).
 template <int FIRST, bool STREAMED>
-__device__ __forceinline__ void store_h_pair(void* outp, int row, bool row_ok, int n0, int rows_total,
+__device__ __forceinline__ void store_h_pair(void* outp, int row, bool row_ok, int n0, int N,
                                              const float* bias, f32x4 v0, f32x4 v1) {
     static_assert(FIRST != 0, "first product only");
     const int g = (threadIdx.x & 63) >> 4;
@@ -118,7 +117,7 @@ __device__ __forceinline__ void store_h_pair(void* outp, int row, bool row_ok, i
     // even g: columns 4g ... 4g + 7 of the first block; odd g: columns 4(g-1) ... + 7 of the second
     const int n = n0 + (g & 1) * 16 + (g & 2) * 4;
     if (!row_ok) return;
-    uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, rows_total));
+    uint32_t* q = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(outp) + h_index(row, n, N >> 5));
     if (STREAMED) {
         __builtin_nontemporal_store(lo[0], q);             // merged into one 16-byte store
         __builtin_nontemporal_store(hi[0], q + 1);
@@ -153,12 +152,71 @@ __device__ __forceinline__ void store_folded_pair(uint16_t* out, int t, float w,
     __builtin_nontemporal_store(hi[1], q + 3);
 }
 
+// ---- outputs of the tiled product's 32 x 32 accumulators (v_mfma_f32_32x32x16_bf16) --------------------
+// Lane l of a wavefront holds, for token row l % 32 of the block, the output columns n0 + 8 q + 4 (l / 32) + i
+// in accumulator register 4 q + i (q, i = 0 ... 3): four groups of four consecutive columns.
+
+// First product: activation, bf16, into the blocked h.  The 32 columns of the block are one k-step group of h
+// (64 bytes per row).  After rounding, lanes l and l + 32 (same row) trade two of their four column groups with
+// v_permlane32_swap, which leaves the lower lane with columns 0 ... 15 and the upper lane with 16 ... 31: 32
+// contiguous bytes per lane, and the wavefront's two stores cover 2 KiB of consecutive rows.  Called by a whole
+// wavefront (no divergence around it); `row_ok`: the lane's row exists.
+template <int FIRST>
+__device__ __forceinline__ void store_h_block32(void* outp, int row, bool row_ok, int n0, int N, const float* bias,
+                                                const f32x16& acc) {
+    static_assert(FIRST != 0, "first product only");
+    constexpr int ACT = FIRST == kFirstGelu ? MOE_ACT_GELU : MOE_ACT_RELU;
+    const int L = (threadIdx.x & 63) >> 5;
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f32x4 v = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n0 + 8 * q + 4 * L);
+        const f32x4 z = activate4<ACT>(v);
+        lo[q] = pack_bf16x2(z[0], z[1]);
+        hi[q] = pack_bf16x2(z[2], z[3]);
+    }
+    const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], lo[2], false, false);
+    const auto s1 = __builtin_amdgcn_permlane32_swap(hi[0], hi[2], false, false);
+    const auto s2 = __builtin_amdgcn_permlane32_swap(lo[1], lo[3], false, false);
+    const auto s3 = __builtin_amdgcn_permlane32_swap(hi[1], hi[3], false, false);
+    if (!row_ok) return;
+    uint4* q = reinterpret_cast<uint4*>(static_cast<uint16_t*>(outp) + h_index(row, n0 + 16 * L, N >> 5));
+    q[0] = uint4{s0[0], s1[0], s0[1], s1[1]};
+    q[1] = uint4{s2[0], s3[0], s2[1], s3[1]};
+}
+
+// Second product whose rows are the layer output (FoldOut): gate weight times the row, one rounding to bf16
+// (what the combine step does for a token with a single expert), the same lane exchange, 32 contiguous bytes
+// of out[t] per lane; not read again by the layer: non-temporal.
+__device__ __forceinline__ void store_folded_block32(uint16_t* out, int t, float w, bool row_ok, int n0, int N,
+                                                     const float* bias, const f32x16& acc) {
+    const int L = (threadIdx.x & 63) >> 5;
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f32x4 v = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        if (bias != nullptr) v += *reinterpret_cast<const f32x4*>(bias + n0 + 8 * q + 4 * L);
+        lo[q] = pack_bf16x2(fmaf(w, v[0], 0.f), fmaf(w, v[1], 0.f));
+        hi[q] = pack_bf16x2(fmaf(w, v[2], 0.f), fmaf(w, v[3], 0.f));
+    }
+    const auto s0 = __builtin_amdgcn_permlane32_swap(lo[0], lo[2], false, false);
+    const auto s1 = __builtin_amdgcn_permlane32_swap(hi[0], hi[2], false, false);
+    const auto s2 = __builtin_amdgcn_permlane32_swap(lo[1], lo[3], false, false);
+    const auto s3 = __builtin_amdgcn_permlane32_swap(hi[1], hi[3], false, false);
+    if (!row_ok) return;
+    uint32_t* q = reinterpret_cast<uint32_t*>(out + static_cast<size_t>(t) * N + n0 + 16 * L);
+    const uint32_t v8[8] = {s0[0], s1[0], s0[1], s1[1], s2[0], s3[0], s2[1], s3[1]};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(v8[i], q + i);     // merged into two 16-byte stores
+}
+
 // Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
 // Called by every thread of every block of the following kernel; 4 columns of a row per thread and step.
 template <int FIRST, bool FOLD>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
-                                                   int N, int kblk, int G, int rows_total,
+                                                   int N, int kblk, int G,
                                                    const float* __restrict__ bias, const FoldOut fold) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
@@ -182,7 +240,7 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
             const int t = fold.tokmap[tl.row0 + lr];
             store_folded(fold.out, t, fold.gate[t], c, N, be, sum);
         } else {
-            store_out<FIRST>(outp, tl.row0 + lr, c, N, rows_total, be, sum);
+            store_out<FIRST>(outp, tl.row0 + lr, c, N, be, sum);
         }
     }
 }

@@ -2,9 +2,17 @@
 
 Bars: routing indices, counts, offsets, hot masks and permutations bit-exact
 (tokens whose fp64 top-(k+1) logit margin is below 1e-4 are listed and excluded from the index
-comparison); floating-point outputs within 1e-2 under  |got - ref| / max(|ref|, rms(ref))
-against the oracle run at the layer's storage precision for the hidden activation, and within
-1e-2 of max|ref| (normalised max error) against the oracle that never rounds it.
+comparison).  Floating-point outputs, every element, with e = |got - ref| / max(|ref|, rms of the
+element's own row of ref):
+  - against the oracle that stores the hidden activation in the layer's storage type (what a bf16 run
+    holds between the two linear layers, Section 4.1): e <= 1e-2;
+  - against the oracle that never rounds it (fp64 throughout): every row within 1e-2 as a vector
+    (||d||_2 / ||ref||_2 and max|d| / max|ref| per row), and every element e <= 1.5e-2.  The one bf16
+    rounding of the hidden activation gives each output element a random error of 1.66e-3 of its row's
+    rms, the final rounding up to 2^-9 of the element: the largest of N elements then sits near
+    (sqrt(2 ln N) * 1.66e-3 + 2^-9) -- 1.0e-2 at 10^5 elements, 1.2e-2 at the 3.4 * 10^7 outputs of the
+    largest preset -- whatever the implementation; the share of elements above 1e-2 is logged.
+fp32 layers: 1e-5 on all of these.
 """
 import functools
 import sys
@@ -18,7 +26,9 @@ from oracle import moe_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
-TOL = 1e-2
+TOL = 1e-2               # spec bar
+TOL_EXACT_ELEM = 1.5e-2  # element-wise against the never-rounding oracle (see the module docstring)
+TOL_F32 = 1e-5
 MARGIN = 1e-4
 
 
@@ -71,6 +81,10 @@ EXTRA = {
     # 256-CU device) and a top-1 layer of that size (folded output, tiled and streaming experts together)
     "tokens_8k": wl.MoEConfig("tokens_8k", T=8192 + 40, d_model=128, d_ff=256, E=96, k=2, dtype="bf16",
                               renormalize=True, seed=41, zipf_s=1.1, gate_std=0.3),
+    # several full scheduling rounds of the tiled kernel, compared in full: about 65 row tiles x 8 column tiles
+    # (two rounds of 256 units and a cut left-over round) in the first product, 65 x 4 in the second
+    "rounds_full": wl.MoEConfig("rounds_full", T=16640 + 77, d_model=1024, d_ff=2048, E=3, k=1, dtype="bf16",
+                                renormalize=False, seed=43, zipf_s=1.0),
     "tokens_12k_top1": wl.MoEConfig("tokens_12k_top1", T=12000, d_model=128, d_ff=256, E=40, k=1, dtype="bf16",
                                     renormalize=False, seed=42, zipf_s=1.2, gate_std=0.3),
     # GeLU as the trailing activation (Section 3.4): fp32 kernel, streaming kernel (rows in LDS / split
@@ -131,8 +145,9 @@ SMALL = ["tiny_f32", "ragged_bf16", "ragged_f32", "one_expert", "single_token", 
          "many_experts", "experts_200", "max_experts", "all_to_one", "gelu_f32", "gelu_ragged", "gelu_wide", "gelu_all_to_one",
          "bias_f32", "bias_ragged", "bias_wide_gelu", "bias_all_to_one"] + list(RANDOM)
 MEDIUM = ["switch_base", "switch_large_skew", "switch_large_skew_matched", "switch_base_8", "switch_base_128",
-          "tokens_8k", "tokens_12k_top1"]
-LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4"]
+          "tokens_8k", "tokens_12k_top1", "rounds_full"]
+LARGE = ["nllb_decode", "nllb_prefill_skew", "nllb_decode_b1", "nllb_decode_b4", "nllb_decode_b16"]
+FULL = ["switch_base", "rounds_full"]      # larger configs whose values are compared in full by the per-call tests
 
 _layers = {}
 
@@ -169,16 +184,29 @@ def dev_i32(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
 
 
-def check_values(got, ref_store, ref_exact, what):
-    e1 = orc.rel_error(got, ref_store)
-    nmax = float(np.abs(got - ref_exact).max() / max(np.abs(ref_exact).max(), 1e-30))
+def check_values(got, ref_store, ref_exact, what, f32=False, quiet=False):
+    """got, ref_*: [rows, d].  Returns the statistics so that a caller that streams a large comparison
+    through here in pieces can report the overall figures."""
+    got = np.asarray(got, np.float64)
+    e_store = float(orc.rel_error_rows(got, ref_store).max())
+    ex = orc.rel_error_rows(got, ref_exact)
+    e_exact = float(ex.max())
+    above = int(np.count_nonzero(ex > TOL))
+    row_l2 = float(orc.row_error_norms(got, ref_exact).max())
+    absref = np.abs(ref_exact).max(axis=1)
+    row_max = float((np.abs(got - ref_exact).max(axis=1) / np.where(absref > 0, absref, 1.0)).max())
     rms = float(np.sqrt(np.mean((got - ref_exact) ** 2)) / max(np.sqrt(np.mean(ref_exact ** 2)), 1e-30))
-    say(f"[values] {what}: max rel (storage-precision oracle) {e1.max():.3e}; vs exact oracle: "
-        f"normalised max {nmax:.3e}, rms ratio {rms:.3e}, elementwise max "
-        f"{orc.rel_error(got, ref_exact).max():.3e}")
-    assert e1.max() <= TOL, what
-    assert nmax <= TOL, what
-    assert rms <= 5e-3, what
+    old = float(orc.rel_error(got, ref_exact).max())         # the statistic with one rms for the whole array
+    if not quiet:
+        say(f"[values] {what}: element-wise max vs storage-precision oracle {e_store:.3e}; vs exact oracle: "
+            f"element-wise max {e_exact:.3e} ({above} of {ex.size} above {TOL:g}), worst row L2 {row_l2:.3e}, "
+            f"worst row max-norm {row_max:.3e}, rms ratio {rms:.3e}; (global-rms statistic {old:.3e})")
+    t_store, t_vec, t_elem = (TOL_F32,) * 3 if f32 else (TOL, TOL, TOL_EXACT_ELEM)
+    assert e_store <= t_store, what
+    assert row_l2 <= t_vec and row_max <= t_vec, what
+    assert e_exact <= t_elem, what
+    assert rms <= (TOL_F32 if f32 else 5e-3), what
+    return dict(e_store=e_store, e_exact=e_exact, above=above, n=ex.size, row_l2=row_l2, row_max=row_max)
 
 
 # ------------------------------------------------------------------------------ route
@@ -283,10 +311,10 @@ def test_expert_ffn(gpu_lib, name):
     torch.cuda.synchronize()
     y = L.y_perm.cpu().numpy().astype(np.float64)
     assert np.isfinite(y).all(), "rows of active experts left unwritten"
-    per = 10 ** 9 if name in SMALL + ["switch_base"] else 12
+    per = 10 ** 9 if name in SMALL + FULL else 12
     rows = sample_rows(r, cfg, per, np.random.default_rng(5))
     pos, ref_s, ref_x = oracle_ffn_rows(r, cfg, rows)
-    check_values(y[pos], ref_s, ref_x, f"y_perm {name} ({len(pos)} rows)")
+    check_values(y[pos], ref_s, ref_x, f"y_perm {name} ({len(pos)} rows)", f32=cfg.dtype == "f32")
     # masked run: rows of masked-out experts stay untouched
     mask_np = (np.arange(cfg.E) % 2 == 0).astype(np.uint8)
     L.y_perm.fill_(float("nan"))
@@ -376,7 +404,7 @@ def test_layer_forward(gpu_lib, name):
     r = oracle_route(name)
     L = device_layer(gpu_lib, name)
     low = r["margin"] < MARGIN
-    n_tok = 10 ** 9 if name in SMALL + ["switch_base"] else 160
+    n_tok = 10 ** 9 if name in SMALL + FULL else 160
     toks = pick_tokens(r, cfg, n_tok, np.random.default_rng(9))
     toks = toks[~low[toks]]
     hd = "bf16" if cfg.dtype == "bf16" else None
@@ -402,18 +430,34 @@ def test_layer_forward(gpu_lib, name):
             assert np.array_equal(L.perm.cpu().numpy(), r["perm"])
             assert np.array_equal(L.hot_mask.cpu().numpy(),
                                   np.ones(cfg.E, np.uint8) if mask_ref is None else mask_ref)
+        else:
+            # a low-margin token may legitimately sit with another expert: histogram, permutation and hot mask
+            # must then be the ones that belong to the indices the GPU chose
+            counts_g = np.bincount(idx.reshape(-1), minlength=cfg.E)
+            assert np.array_equal(L.counts.cpu().numpy(), counts_g)
+            assert np.array_equal(L.perm.cpu().numpy(), orc.stable_permutation_fast(idx, cfg.E)[0])
+            if Harg >= 0:
+                assert np.array_equal(L.hot_mask.cpu().numpy(), orc.hot_mask_top_h(counts_g, Harg))
+            elif mask_arg is not None:
+                assert np.array_equal(L.hot_mask.cpu().numpy(), mask_arg.astype(np.uint8))
+            else:
+                assert np.array_equal(L.hot_mask.cpu().numpy(), np.ones(cfg.E, np.uint8))
         ref_s = oracle_layer_rows(r, cfg, toks, mask_ref, ys_s)
         ref_x = oracle_layer_rows(r, cfg, toks, mask_ref, ys_x)
         if np.abs(ref_x).max() == 0:
             assert np.all(got[toks] == 0)
         else:
-            check_values(got[toks], ref_s, ref_x, f"out {name} [{label}] ({len(toks)} tokens)")
+            check_values(got[toks], ref_s, ref_x, f"out {name} [{label}] ({len(toks)} tokens)", f32=cfg.dtype == "f32")
     assert np.array_equal(outs["hot mask given"], outs["top-H on device"])
     # the two shares add up to the whole layer (each is rounded to storage once)
+    # Besides the final rounding of each share, an element may differ by summation order: which large-expert tiles
+    # fall into the tiled kernel's last scheduling round, and are summed in K-slices, depends on how many tiles the
+    # share has (see test_expert_ffn: up to 1e-3 of the row's rms through a flipped rounding of h).
     s = outs["hot mask given"] + outs["cold share"]
     ulp = 2.0 ** -7 if cfg.dtype == "bf16" else 2.0 ** -22
+    row_rms = np.sqrt(np.mean(outs["full"] ** 2, axis=1, keepdims=True))
     assert np.all(np.abs(s - outs["full"]) <= 2 * ulp * (np.abs(outs["hot mask given"]) +
-                                                         np.abs(outs["cold share"]) + 1e-30) + 1e-30)
+                                                         np.abs(outs["cold share"]) + 1e-30) + 1e-3 * row_rms + 1e-30)
     # determinism of the whole path
     L.forward()
     torch.cuda.synchronize()
@@ -421,6 +465,75 @@ def test_layer_forward(gpu_lib, name):
     L.forward()
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.uint8), L.out.view(torch.uint8))
+
+
+# ------------------------------------------------------------------------------ full size, every element
+@pytest.mark.parametrize("name", ["switch_large_skew", "nllb_decode", "nllb_decode_b16", "nllb_prefill_skew"])
+def test_full_size_every_element(gpu_lib, name):
+    """The large presets at full size, in the launch configuration the bench times: every row of y_perm
+    (moe_expert_ffn on the oracle's permuted rows) and every token of out (moe_layer_forward: the whole layer,
+    and the hot share where the preset defines one) against the oracle in both of its modes.  The oracle's
+    expert outputs are computed once per expert, compared with y_perm at once and accumulated, weighted by
+    the gates, into the layer outputs (Section 2.1: the experts' outputs are weighted, summed and put back
+    in token order)."""
+    from paper_2405_18832_amd.device_layer import to_device
+    cfg = CFG(name)
+    say(f"[case] every element, {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    low = r["margin"] < MARGIN
+    xp = orc.permute_tokens(r["x"], r["perm"], cfg.k)
+    L.y_perm.fill_(float("nan"))
+    L.expert_ffn(x_perm=to_device(xp, cfg.dtype, L.device), offsets=dev_i32(r["offsets"]))
+    torch.cuda.synchronize()
+    y = L.y_perm.cpu().numpy()
+    assert np.isfinite(y).all()
+    hot = orc.hot_mask_top_h(r["counts"], cfg.H) if cfg.H is not None else None
+    outs = {}
+    for label, mask in (("full", None),) + ((("hot mask given", hot),) if hot is not None else ()):
+        L.out.fill_(float("nan"))
+        L.forward(mask=None if mask is None else torch.from_numpy(mask.astype(np.uint8)).cuda(), debug=True)
+        torch.cuda.synchronize()
+        outs[label] = (mask, L.out_numpy())
+        assert np.array_equal(L.topk_idx.cpu().numpy()[~low], r["idx"][~low])
+    ref = {label: [np.zeros((cfg.T, cfg.d_model)), np.zeros((cfg.T, cfg.d_model))] for label in outs}
+    worst = dict(e_store=0.0, e_exact=0.0, above=0, n=0, row_l2=0.0, row_max=0.0)
+
+    def fold(st):
+        for key in ("e_store", "e_exact", "row_l2", "row_max"):
+            worst[key] = max(worst[key], st[key])
+        worst["above"] += st["above"]
+        worst["n"] += st["n"]
+
+    tokens_of = r["perm"] // cfg.k
+    slot_of = r["perm"] % cfg.k
+    for e in range(cfg.E):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        if hi == lo:
+            continue
+        we = expert_cached(name, e)
+        ys = orc.expert_ffn(xp[lo:hi], we[0], we[1], "bf16", cfg.activation, *we[2:4])
+        yx = orc.expert_ffn(xp[lo:hi], we[0], we[1], None, cfg.activation, *we[2:4])
+        fold(check_values(y[lo:hi], ys, yx, f"y_perm {name} expert {e} ({hi - lo} rows)", quiet=hi - lo < 64))
+        g = r["g"][tokens_of[lo:hi], slot_of[lo:hi]][:, None]
+        for label, (mask, _) in outs.items():
+            if mask is None or mask[e]:
+                ref[label][0][tokens_of[lo:hi]] += g * ys       # a token meets an expert at most once
+                ref[label][1][tokens_of[lo:hi]] += g * yx
+    say(f"[values] y_perm {name}, all {worst['n']} elements: element-wise max vs storage-precision oracle "
+        f"{worst['e_store']:.3e}, vs exact oracle {worst['e_exact']:.3e} ({worst['above']} above {TOL:g}), worst row "
+        f"L2 {worst['row_l2']:.3e}, worst row max-norm {worst['row_max']:.3e}")
+    ok = np.nonzero(~low)[0]
+    for label, (mask, got) in outs.items():
+        worst = dict(e_store=0.0, e_exact=0.0, above=0, n=0, row_l2=0.0, row_max=0.0)
+        for c0 in range(0, len(ok), 2048):
+            t = ok[c0:c0 + 2048]
+            fold(check_values(got[t], ref[label][0][t], ref[label][1][t], f"out {name} [{label}] tokens {c0}...",
+                              quiet=True))
+        say(f"[values] out {name} [{label}], all {worst['n']} elements of {len(ok)} tokens: element-wise max vs "
+            f"storage-precision oracle {worst['e_store']:.3e}, vs exact oracle {worst['e_exact']:.3e} "
+            f"({worst['above']} above {TOL:g}), worst row L2 {worst['row_l2']:.3e}, worst row max-norm "
+            f"{worst['row_max']:.3e}")
 
 
 @pytest.mark.gpu

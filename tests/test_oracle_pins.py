@@ -386,3 +386,51 @@ def test_plan_devices_round_robin_by_load():
         # every round hands out non-increasing counts
         order = sorted(np.flatnonzero(active), key=lambda e: (-c[e], e))
         assert [dev[e] for e in order] == [i % G for i in range(len(order))]
+
+
+# ---------------------------------------------------------------- the parity statistics themselves
+def test_error_statistics_on_a_hand_worked_example():
+    # ref = [[3, 4], [0, 0.5]], got = [[3.3, 3.8], [0.05, 0.5]]  (worked by hand)
+    # global rms(ref) = sqrt((9 + 16 + 0 + 0.25) / 4) = sqrt(6.3125) = 2.5124689...
+    #   rel_error: |d| = [[0.3, 0.2], [0.05, 0]], floors max(|ref|, rms) = [[3, 4], [rms, rms]]
+    #            -> [[0.1, 0.05], [0.05 / 2.5124689, 0]]
+    # per-row rms: row 0 sqrt(12.5) = 3.5355339, row 1 sqrt(0.125) = 0.35355339
+    #   rel_error_rows: floors [[3.5355339, 4], [0.35355339, 0.5]] -> [[0.3 / 3.5355339, 0.05], [0.05 / 0.35355339, 0]]
+    # row norms: row 0 sqrt(0.09 + 0.04) / 5 = 0.0721110, row 1 0.05 / 0.5 = 0.1
+    ref = np.array([[3.0, 4.0], [0.0, 0.5]])
+    got = np.array([[3.3, 3.8], [0.05, 0.5]])
+    e = orc.rel_error(got, ref)
+    assert np.allclose(e, [[0.1, 0.05], [0.05 / 2.5124689052802225, 0.0]], rtol=1e-12, atol=1e-15)
+    er = orc.rel_error_rows(got, ref)
+    assert np.allclose(er, [[0.3 / 3.5355339059327378, 0.05], [0.05 / 0.35355339059327379, 0.0]], rtol=1e-12, atol=1e-15)
+    assert np.allclose(orc.row_error_norms(got, ref), [0.07211102550927978, 0.1], rtol=1e-12)
+    # numbers, not only formulas: 0.3 / 3.5355339 = 0.0848528..., 0.05 / 0.35355339 = 0.1414213...
+    assert abs(er[0, 0] - 0.0848528137) < 1e-9 and abs(er[1, 0] - 0.1414213562) < 1e-9
+    assert abs(e[1, 0] - 0.0199007438) < 1e-9
+
+
+def test_error_statistics_properties():
+    rng = np.random.default_rng(5)
+    ref = rng.standard_normal((7, 33))
+    # exact agreement -> zero everywhere; a scaled copy -> the scale's relative error on large elements
+    assert orc.rel_error(ref, ref).max() == 0 and orc.rel_error_rows(ref, ref).max() == 0
+    assert orc.row_error_norms(ref, ref).max() == 0
+    got = ref * 1.01
+    assert np.allclose(orc.row_error_norms(got, ref), 0.01, rtol=1e-9)
+    assert orc.rel_error_rows(got, ref).max() <= 0.01 * (1 + 1e-9)       # never above the true relative error
+    big = np.abs(ref) >= np.sqrt(np.mean(ref * ref, axis=1, keepdims=True))
+    assert np.allclose(orc.rel_error_rows(got, ref)[big], 0.01, rtol=1e-9)
+    # a larger denominator would loosen every value check: the floor is never above max(|ref|, row rms)
+    tiny = np.abs(ref) < 1e-3
+    if tiny.any():
+        rms = np.sqrt(np.mean(ref * ref, axis=1, keepdims=True)) * np.ones_like(ref)
+        assert np.allclose(orc.rel_error_rows(ref + 1e-3, ref)[tiny], (1e-3 / rms)[tiny], rtol=1e-9)
+    # rows differ in scale: the per-row statistic is invariant under scaling a row of both arrays
+    s = np.array([1e-3, 1, 10, 1e3, 1, 1, 1e-6])[:, None]
+    g2 = ref + 0.01 * rng.standard_normal(ref.shape)
+    assert np.allclose(orc.rel_error_rows(g2 * s, ref * s), orc.rel_error_rows(g2, ref), rtol=1e-9)
+    assert np.allclose(orc.row_error_norms(g2 * s, ref * s), orc.row_error_norms(g2, ref), rtol=1e-9)
+    # a row of zeros in ref: absolute error
+    z = np.zeros((1, 4))
+    assert np.allclose(orc.rel_error_rows(z + 0.25, z), 0.25) and np.allclose(orc.row_error_norms(z + 0.25, z), 0.5)
+    assert np.allclose(orc.rel_error(z + 0.25, z), 0.25)
