@@ -27,7 +27,7 @@
  *  - Every entry point works on the calling thread's current HIP device.  The first call on a
  *    device (or moe_init) sets the kernels up for it once, under a lock; after that, calls from
  *    several host threads and on several devices are independent, except where a call says
- *    otherwise (moe_set_profile_events).
+ *    otherwise (moe_set_profile_events, moe_layer_forward_noalloc).
  *  - Row-major everywhere, last index contiguous.  dtype selects the storage type
  *    of x, w_gate, W1, W2, x_perm and out; products are accumulated in fp32.
  *    Gate weights, logits margins and y_perm are always fp32; indices are int32.
@@ -254,6 +254,26 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
                                     const float* b2, const uint8_t* mask, int32_t H, void* out, int32_t* topk_idx,
                                     float* topk_w, int32_t* counts, int32_t* perm, uint8_t* hot_mask_out, void* ws,
                                     size_t ws_bytes, void* stream);
+
+/*
+ * moe_layer_forward for callers that must not allocate device memory and have no workspace to pass: code
+ * running under HIP graph capture, tight serving loops (a decoder step per call), harnesses that forbid
+ * hipMalloc.  The layer's workspace is a static device array inside the library, MOE_NOALLOC_MAX_WORKSPACE
+ * bytes on every GPU the library runs on, held until the process ends; the call makes no hipMalloc / hipFree
+ * and calls no allocating routine.  Shapes whose moe_workspace_bytes() exceeds that size are refused with
+ * MOE_ERR_WORKSPACE before anything is launched (decoder steps of the paper's models, up to 127 tokens of an
+ * NLLB-MoE-shaped layer, need 4 to 7 MiB; layers of 128 tokens or more ask for 64 MiB of partial-tile space
+ * and do not fit).  Arguments as moe_layer_forward, without the optional outputs;
+ * the result is bit-identical to moe_layer_forward on the same inputs.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different
+ * streams or threads) race and give undefined results; calls on one stream, or ordered by events, are fine.
+ * Nothing from an earlier call is reused: the layer clears the counters it needs in its own kernels.
+ */
+#define MOE_NOALLOC_MAX_WORKSPACE (16u << 20)
+size_t moe_noalloc_max_workspace(void);     /* = MOE_NOALLOC_MAX_WORKSPACE */
+moe_status moe_layer_forward_noalloc(const moe_shape* shape, const void* x, const void* w_gate,
+                                     const float* gate_bias, const void* w1, const void* w2,
+                                     const uint8_t* mask, int32_t H, void* out, void* stream);
 
 #ifdef __cplusplus
 }

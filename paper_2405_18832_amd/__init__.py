@@ -20,7 +20,7 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP
 MOE_F32, MOE_BF16 = 0, 1
 MOE_MAX_K, MOE_MAX_E = 8, 1024
 
-EXPORTS = ["moe_init",
+EXPORTS = ["moe_init", "moe_noalloc_max_workspace", "moe_layer_forward_noalloc",
            "moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
            "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts",
@@ -59,6 +59,10 @@ def load() -> ctypes.CDLL:
     sp = ctypes.POINTER(moe_shape)
     lib.moe_init.restype = ctypes.c_int
     lib.moe_init.argtypes = []
+    lib.moe_noalloc_max_workspace.restype = sz
+    lib.moe_noalloc_max_workspace.argtypes = []
+    lib.moe_layer_forward_noalloc.restype = ctypes.c_int
+    lib.moe_layer_forward_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.moe_status_string.restype = ctypes.c_char_p
     lib.moe_status_string.argtypes = [ctypes.c_int]
     lib.moe_workspace_bytes.restype = sz
@@ -141,6 +145,16 @@ def _check(status: int, where: str) -> None:
 
 def moe_init() -> None:
     _check(load().moe_init(), "moe_init")
+
+
+def moe_noalloc_max_workspace() -> int:
+    return int(load().moe_noalloc_max_workspace())
+
+
+def moe_layer_forward_noalloc(shape, x, w_gate, gate_bias, w1, w2, mask, H, out, stream=None) -> None:
+    _check(load().moe_layer_forward_noalloc(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(w1),
+                                            _ptr(w2), _ptr(mask), int(H), _ptr(out), _stream(stream)),
+           "moe_layer_forward_noalloc")
 
 
 def moe_workspace_bytes(shape: moe_shape) -> int:

@@ -8,10 +8,17 @@
 
 using namespace moe;
 
+// Scratch memory of the entry point that allocates nothing (moe_layer_forward_noalloc): one array per GPU that
+// loads this library, held until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress; the device address it yields (per device) is what kernels and host calls are given.
+constexpr size_t kScratchBytes = static_cast<size_t>(MOE_NOALLOC_MAX_WORKSPACE);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 std::mutex g_setup_mutex;
 std::atomic<bool> g_device_ready[kMaxDevices];
+void* g_scratch_ptr[kMaxDevices] = {nullptr};     // device address of `scratch` on each device (set under the lock)
 
 moe_status check_shape(const moe_shape* s) {
     if (s == nullptr) return MOE_ERR_INVALID_ARG;
@@ -61,6 +68,10 @@ hipError_t ensure_ready() {
     if ((e = configure_ffn_kernels(dev)) != hipSuccess) return e;
     if ((e = configure_tile_kernels(dev)) != hipSuccess) return e;
     if ((e = configure_route_kernels(dev)) != hipSuccess) return e;
+    // this device's copy of the scratch array (each GPU has its own, at its own address)
+    void* p = nullptr;
+    if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
     g_device_ready[dev].store(true, std::memory_order_release);
     return hipSuccess;
 }
@@ -314,6 +325,24 @@ moe_status moe_layer_forward_biased(const moe_shape* shape, const void* x, const
     if (folded) return MOE_OK;                 // the second product has written `out`
     e = launch_combine(*shape, at<float>(ws, L.y_perm), inv, idx, gate, used, out, hs);
     return from_hip(e);
+}
+
+size_t moe_noalloc_max_workspace(void) { return kScratchBytes; }
+
+moe_status moe_layer_forward_noalloc(const moe_shape* shape, const void* x, const void* w_gate, const float* gate_bias,
+                                     const void* w1, const void* w2, const uint8_t* mask, int32_t H, void* out,
+                                     void* stream) {
+    moe_status st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    // the layer's whole workspace must fit into the static array
+    if (ws_layout(*shape).total > kScratchBytes) return MOE_ERR_WORKSPACE;
+    if (ensure_ready() != hipSuccess) return MOE_ERR_HIP;
+    void* ws = g_scratch_ptr[current_device_index()];      // the device address, never the array's name
+    if (ws == nullptr) return MOE_ERR_HIP;
+    // Everything the layer reads from its workspace it has written earlier in the same call (counters and
+    // histograms are cleared by its kernels), so the contents a previous call left behind do not matter.
+    return moe_layer_forward_biased(shape, x, w_gate, gate_bias, w1, nullptr, w2, nullptr, mask, H, out, nullptr,
+                                    nullptr, nullptr, nullptr, nullptr, ws, kScratchBytes, stream);
 }
 
 }  // extern "C"

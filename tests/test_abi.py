@@ -143,3 +143,21 @@ def test_binding_raises_on_error():
     with pytest.raises(moe.MoEError) as ei:
         moe.moe_combine(shape(), FAKE, FAKE, FAKE, FAKE, None, None, stream=0)
     assert ei.value.status == moe.MOE_ERR_INVALID_ARG
+
+
+def test_noalloc_entry_point_refuses_before_any_gpu_call():
+    """The entry point that allocates nothing checks the shape and the size of the workspace it would need
+    against its static array on the host, before anything touches a GPU."""
+    lib = moe.load()
+    assert moe.moe_noalloc_max_workspace() == 16 << 20
+
+    def status(s):
+        return lib.moe_layer_forward_noalloc(ctypes.byref(s), FAKE, FAKE, None, FAKE, FAKE, None, -1, FAKE, None)
+
+    assert status(shape(k=9)) == moe.MOE_ERR_INVALID_ARG           # k > E
+    assert status(shape(d_model=48)) == moe.MOE_ERR_UNSUPPORTED    # bf16 needs multiples of 32
+    big = shape(T=4096, d_model=1024, d_ff=4096, E=128, k=1)
+    assert moe.moe_workspace_bytes(big) > moe.moe_noalloc_max_workspace()
+    assert status(big) == moe.MOE_ERR_WORKSPACE
+    # decoder steps of the NLLB-shaped layer fit
+    assert moe.moe_workspace_bytes(shape(T=32, d_model=2048, d_ff=8192, E=128, k=2)) < moe.moe_noalloc_max_workspace()
