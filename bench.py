@@ -112,6 +112,35 @@ def config_of(name: str):
             else wl.CONFIGS.get(name) or wl.EXTRA_CONFIGS[name])
 
 
+def library_gemm_context(M: int, d: int, f: int) -> dict:
+    """Context, not a target: the ROCm BLAS library's dense bf16 GEMM (through torch.matmul) on the shapes of the
+    two products of the large experts taken together, M rows, with normal random operands (the second product's
+    row operand passed through ReLU, as the layer's is).  The chip lowers its clock under matrix load, by an
+    amount that depends on the operand values, so a dense GEMM of the same shape and value distribution is the
+    yardstick for what fraction of the published peak is reachable at all."""
+    import torch
+    out = {}
+    for tag, (N, K, relu) in {"x_w1": (f, d, False), "h_w2": (d, f, True)}.items():
+        a = torch.randn(M, K, device="cuda:0", dtype=torch.bfloat16)
+        if relu:
+            a = torch.relu(a)
+        b = torch.randn(N, K, device="cuda:0", dtype=torch.bfloat16) / K ** 0.5
+        for _ in range(3):
+            c = a @ b.t()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            c = a @ b.t()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        tf = 2.0 * M * N * K / (us * 1e-6) / 1e12
+        out[tag] = {"M": M, "N": N, "K": K, "us": us, "tflops": tf, "frac_of_peak": tf / PEAK_BF16_TFLOPS}
+        del a, b, c
+    torch.cuda.empty_cache()
+    return out
+
+
 def measure(name: str, share: str, K: int, W: int, copies_arg: int = 0, cpu_baseline: bool = False,
             measure_fetch: bool = False, breakdown: bool = True) -> dict:
     """One workload: W warm-up steps, exactly K timed steps, then the same K steps again with HIP events
@@ -337,7 +366,18 @@ def measure(name: str, share: str, K: int, W: int, copies_arg: int = 0, cpu_base
             f"max rel err {err:.3e} (per-row normalised), worst row L2 err {vec:.3e}; vs the oracle that stores the "
             f"hidden activation in bf16: {err_s if err_s is None else format(err_s, '.3e')}")
 
-    res = {"value": tokens_s, "ms_per_step": ms_step, "dtype": cfg.dtype,
+    ctx = None
+    if cpu_baseline and rows_b > 0 and roof is not None and roof["bound"] == "mfma":
+        del L
+        L = None
+        gc.collect()
+        torch.cuda.empty_cache()
+        ctx = {"library_gemm": library_gemm_context(rows_b, d, f)}
+        log("[bench] context: library bf16 GEMM on the large experts' rows taken together: "
+            + ", ".join(f"{k_} {v['us']:.0f} us = {v['tflops']:.0f} TFLOP/s ({v['frac_of_peak']:.3f} of peak)"
+                        for k_, v in ctx["library_gemm"].items()))
+
+    res = {"value": tokens_s, "ms_per_step": ms_step, "dtype": cfg.dtype, "context": ctx,
            "config": {"workload": describe(cfg), "share": share, "weight_copies_rotated": copies},
            "roofline": roof, "cpu_baseline": cpu, "layer": layer}
     del L, cache
@@ -396,7 +436,8 @@ def main() -> int:
     out = {"metric": "MoE-FFN tokens/s", "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": K,
            "warmup": W, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic", "config": head["config"],
-           "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"], "layer": head["layer"]}
+           "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"], "layer": head["layer"],
+           "context": head["context"]}
 
     if args.workload is None:
         # the other presets and the hot-only shares: short steps, so more of them for a steady figure

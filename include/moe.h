@@ -175,6 +175,25 @@ moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double 
                           double bw_b, int32_t* H_out, uint8_t* hot_mask, void* stream);
 
 /*
+ * Auto-tuning of alpha (Section 3.3, the paragraph after Eq. 6: the factor is tuned by running profiled inference
+ * on a small set of past input batches and finding the local optimum among the candidates H, H + 1, H + 2).
+ * Host arithmetic, no GPU, HOST pointers.  The caller runs its past batches with H_b + c hot experts, c = 0 ...
+ * n_candidates - 1 (H_b = moe_select_hot at the current alpha; moe_layer_forward takes H directly) and measures:
+ *   activated [n_batches]                activated experts of each batch (experts with at least one token);
+ *   times     [n_batches, n_candidates]  measured time of batch b with H_b + c hot experts (any unit, > 0).
+ * best_offset_out: the c with the smallest total time over the batches (the smallest such c on equal totals).
+ * alpha_out: the paper leaves open how the chosen candidate becomes a new alpha; here it is the alpha at which
+ * Eq. 6's real-valued H of a batch with the mean number of activated experts is best_offset larger:
+ *   alpha + best_offset / (bw_a / (bw_a + bw_b) * mean(activated)),
+ * evaluated in double precision in this order; alpha itself when best_offset is 0 or no expert was activated.
+ * Either output may be NULL.  MOE_ERR_INVALID_ARG on NULL inputs, n_batches < 1, n_candidates < 1, a negative
+ * count, a time that is not finite and positive, or bandwidths / alpha outside moe_select_hot's domain; nothing
+ * is written then.
+ */
+moe_status moe_tune_alpha(double alpha, double bw_a, double bw_b, int32_t n_batches, const int32_t* activated,
+                          int32_t n_candidates, const double* times, double* alpha_out, int32_t* best_offset_out);
+
+/*
  * Dispatch (Section 2.1 "route each token to the top-k experts"; Section 4.1: drop-less,
  * padding-less).  Stable counting sort of the A assignments by expert:
  *   perm [A]: perm[p] = flat assignment id at sorted position p (experts ascending, inside

@@ -167,6 +167,39 @@ def hot_expert_count(counts, alpha, bw_a, bw_b):
     return max(0, min(int(np.floor(h + 0.5)), E))
 
 
+def tune_alpha(alpha, bw_a, bw_b, activated, times):
+    """Auto-tuning of the scaling factor alpha (Section 3.3, the paragraph after Eq. 6: profiled inference on a
+    small set of past input batches finds the local optimum among the candidates H, H + 1, H + 2).
+
+    activated[b]: number of activated experts of past batch b; times[b][c]: measured time of the layer on batch
+    b with H_b + c hot experts, c = 0 ... C-1, where H_b is Eq. 6 at the current alpha.  The offset c* with the
+    smallest total time over the batches is taken (the smallest such offset when totals are equal).  The paper
+    does not say how the chosen candidate turns into a new alpha; the reading here: the alpha at which Eq. 6's
+    real-valued H, for a batch with the mean number of activated experts, is c* larger than at the current one:
+        alpha_new = alpha + c* / (rho * mean(activated)),   rho = BW_a / (BW_a + BW_b),
+    and alpha stays as it is when c* = 0 or no batch activated any expert.  Returns (alpha_new, c*)."""
+    times = np.asarray(times, F64)
+    activated = np.asarray(activated)
+    B, C = times.shape
+    assert activated.shape == (B,) and B >= 1 and C >= 1
+    totals = np.zeros(C, F64)
+    for b in range(B):              # summed in batch order
+        for c in range(C):
+            totals[c] = totals[c] + times[b, c]
+    best = 0
+    for c in range(1, C):
+        if totals[c] < totals[best]:
+            best = c
+    total_activ = 0
+    for b in range(B):
+        total_activ += int(activated[b])
+    if best == 0 or total_activ == 0:
+        return float(alpha), best
+    rho = float(bw_a) / (float(bw_a) + float(bw_b))
+    mean = float(total_activ) / float(B)
+    return float(alpha) + float(best) / (rho * mean), best
+
+
 def plan_devices(counts, n_devices, skip=None):
     """Load balancing over several expert-holding devices (Section 3.3, last paragraph): the experts
     that have tokens (and are not in `skip`, e.g. the hot set kept on the main device), sorted by

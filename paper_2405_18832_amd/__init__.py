@@ -23,7 +23,7 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 EXPORTS = ["moe_init", "moe_noalloc_max_workspace", "moe_layer_forward_noalloc",
            "moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
            "moe_set_profile_events",
-           "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts",
+           "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts", "moe_tune_alpha",
            "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_biased", "moe_combine",
            "moe_layer_forward", "moe_layer_forward_biased"]
 
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.moe_activation_movement_bytes.restype = sz
     lib.moe_plan_devices.argtypes = [i32, vp, vp, i32, vp]
     lib.moe_plan_devices.restype = ctypes.c_int
+    lib.moe_tune_alpha.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_double, i32, vp, i32, vp, vp, vp]
+    lib.moe_tune_alpha.restype = ctypes.c_int
     lib.moe_fetch_experts.argtypes = [sp, i32, vp, vp, vp, vp]
     lib.moe_fetch_experts.restype = ctypes.c_int
     lib.moe_select_hot.argtypes = [sp, vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, vp, vp, vp]
@@ -204,6 +206,20 @@ def moe_plan_devices(counts, skip, n_devices: int):
     _check(load().moe_plan_devices(int(c.shape[0]), c.ctypes.data, None if k is None else k.ctypes.data,
                                    int(n_devices), out.ctypes.data), "moe_plan_devices")
     return out
+
+
+def moe_tune_alpha(alpha, bw_a, bw_b, activated, times):
+    """activated: host ints [B]; times: host floats [B, C].  Returns (alpha_new, best_offset)."""
+    import numpy as np
+    act = np.ascontiguousarray(np.asarray(activated), dtype=np.int32)
+    t = np.ascontiguousarray(np.asarray(times), dtype=np.float64)
+    if t.ndim != 2 or act.shape != (t.shape[0],):
+        raise ValueError("times must be [n_batches, n_candidates] and activated [n_batches]")
+    a_out, c_out = ctypes.c_double(), ctypes.c_int32()
+    _check(load().moe_tune_alpha(float(alpha), float(bw_a), float(bw_b), int(t.shape[0]), act.ctypes.data,
+                                 int(t.shape[1]), t.ctypes.data, ctypes.addressof(a_out), ctypes.addressof(c_out)),
+           "moe_tune_alpha")
+    return float(a_out.value), int(c_out.value)
 
 
 def moe_fetch_experts(shape, which, src_host, fetch_mask_host, dst_device, stream=None) -> None:

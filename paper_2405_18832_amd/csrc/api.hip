@@ -198,6 +198,43 @@ moe_status moe_select_hot(const moe_shape* shape, const int32_t* counts, double 
                                       static_cast<hipStream_t>(stream)));
 }
 
+moe_status moe_tune_alpha(double alpha, double bw_a, double bw_b, int32_t n_batches, const int32_t* activated,
+                          int32_t n_candidates, const double* times, double* alpha_out, int32_t* best_offset_out) {
+    if (activated == nullptr || times == nullptr || n_batches < 1 || n_candidates < 1) return MOE_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0) || !(bw_a > 0.0) || !(bw_b >= 0.0) || std::isinf(alpha) || std::isinf(bw_a) || std::isinf(bw_b))
+        return MOE_ERR_INVALID_ARG;
+    long long total_activ = 0;
+    for (int b = 0; b < n_batches; ++b) {
+        if (activated[b] < 0) return MOE_ERR_INVALID_ARG;
+        total_activ += activated[b];
+        for (int c = 0; c < n_candidates; ++c) {
+            const double t = times[static_cast<size_t>(b) * n_candidates + c];
+            if (!(t > 0.0) || std::isinf(t)) return MOE_ERR_INVALID_ARG;
+        }
+    }
+    // totals per candidate, summed in batch order; the smallest total wins, the smaller offset on equal totals
+    int best = 0;
+    double best_total = 0.0;
+    for (int c = 0; c < n_candidates; ++c) {
+        double total = 0.0;
+        for (int b = 0; b < n_batches; ++b) total = total + times[static_cast<size_t>(b) * n_candidates + c];
+        if (c == 0 || total < best_total) {
+            best = c;
+            best_total = total;
+        }
+    }
+    double tuned = alpha;
+    if (best != 0 && total_activ != 0) {
+        const double rho = bw_a / (bw_a + bw_b);
+        const double mean = static_cast<double>(total_activ) / static_cast<double>(n_batches);
+        const double step = static_cast<double>(best) / (rho * mean);
+        tuned = alpha + step;
+    }
+    if (alpha_out != nullptr) *alpha_out = tuned;
+    if (best_offset_out != nullptr) *best_offset_out = best;
+    return MOE_OK;
+}
+
 moe_status moe_permute(const moe_shape* shape, const void* x, const int32_t* topk_idx, const int32_t* offsets,
                        int32_t* perm, int32_t* inv_perm, void* x_perm, void* ws, size_t ws_bytes, void* stream) {
     moe_status st = check_shape(shape);

@@ -693,9 +693,12 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
 // the two grouped products over existing tile lists
 // The extra pass over the token rows pays once the layer is large (measured: a gain from 4 M elements of
 // gathered rows on, a small loss at 1.5 M, where the launch costs more than the better-shaped loads save).
+#ifndef MOE_GATHER_MIN_MELEMS
+#define MOE_GATHER_MIN_MELEMS 4      // gathered elements (T * k * d_model), in units of 2^20, from which the pass pays
+#endif
 bool layer_gathers_kmajor(const moe_shape& s) {
     return s.dtype == MOE_BF16 && s.T >= kBigMinRows &&
-           static_cast<long>(s.T) * s.k * s.d_model >= (4L << 20);
+           static_cast<long>(s.T) * s.k * s.d_model >= (static_cast<long>(MOE_GATHER_MIN_MELEMS) << 20);
 }
 
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,

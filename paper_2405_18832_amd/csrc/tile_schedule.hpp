@@ -212,7 +212,11 @@ __device__ __forceinline__ void store_folded_block32(uint16_t* out, int t, float
 }
 
 // Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
-// Called by every thread of every block of the following kernel; 4 columns of a row per thread and step.
+// Called by every thread of every block of the following kernel.  A wavefront takes four consecutive rows of a
+// cut unit at a time (a row of a unit is 256 columns: 4 per lane): what is the same for the whole row -- the unit,
+// its row tile, for a folded output the row's token and gate weight -- is looked up once per wavefront, and the
+// 4 x split loads of partial sums go out together (one row at a time, with a lookup per element, the pass was a
+// chain of dependent trips to memory: 35 of the 50 us of the kernel that did it on the Switch-large preset).
 template <int FIRST, bool FOLD>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
@@ -221,26 +225,43 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
-    constexpr int kQuads = kBigTileRows * kTileCols / 4;
-    const long total = static_cast<long>(s.R) * kQuads;
-    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
-         i += static_cast<long>(gridDim.x) * blockDim.x) {
-        const int ru = static_cast<int>(i / kQuads), q = static_cast<int>(i % kQuads);
+    constexpr int kRowsAtOnce = 4;
+    constexpr int kGroups = kBigTileRows / kRowsAtOnce;         // row groups per unit
+    constexpr size_t kTileFloats = static_cast<size_t>(kBigTileRows) * kTileCols;
+    const int lane = threadIdx.x & 63;
+    const int waves_per_block = blockDim.x >> 6;
+    const int first = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * waves_per_block + (threadIdx.x >> 6));
+    const int nwaves = static_cast<int>(gridDim.x) * waves_per_block;
+    const int total = s.R * kGroups;
+    for (int i = first; i < total; i += nwaves) {              // wave-uniform
+        const int ru = i / kGroups, lr0 = (i % kGroups) * kRowsAtOnce;
         int mt, nt;
         unit_of(s, s.rounds * G + ru, mt, nt);
         const Tile tl = big_tiles[mt];
-        const int lr = q / (kTileCols / 4), c = nt * kTileCols + (q % (kTileCols / 4)) * 4;
-        if (lr >= tl.rows || c >= N) continue;
-        const float* base = partials + (static_cast<size_t>(ru) * s.split * kQuads + q) * 4;
-        f32x4 sum = *reinterpret_cast<const f32x4*>(base);
-        for (int p = 1; p < s.split; ++p)
-            sum += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kQuads * 4);
+        if (lr0 >= tl.rows) continue;
+        const int c = nt * kTileCols + lane * 4;
+        const float* base = partials + static_cast<size_t>(ru) * s.split * kTileFloats + static_cast<size_t>(lr0) * kTileCols + lane * 4;
+        f32x4 sum[kRowsAtOnce];
+        int tok[kRowsAtOnce];
+#pragma unroll
+        for (int q = 0; q < kRowsAtOnce; ++q) {
+            sum[q] = *reinterpret_cast<const f32x4*>(base + q * kTileCols);
+            tok[q] = (FOLD && lr0 + q < tl.rows) ? fold.tokmap[tl.row0 + lr0 + q] : 0;
+        }
+        for (int p = 1; p < s.split; ++p) {                    // in part order, whichever block computed the parts
+#pragma unroll
+            for (int q = 0; q < kRowsAtOnce; ++q)
+                sum[q] += *reinterpret_cast<const f32x4*>(base + static_cast<size_t>(p) * kTileFloats + q * kTileCols);
+        }
         const float* be = bias ? bias + static_cast<size_t>(tl.expert) * N : nullptr;
-        if constexpr (FOLD) {
-            const int t = fold.tokmap[tl.row0 + lr];
-            store_folded(fold.out, t, fold.gate[t], c, N, be, sum);
-        } else {
-            store_out<FIRST>(outp, tl.row0 + lr, c, N, be, sum);
+#pragma unroll
+        for (int q = 0; q < kRowsAtOnce; ++q) {
+            if (lr0 + q >= tl.rows || c >= N) continue;
+            if constexpr (FOLD) {
+                store_folded(fold.out, tok[q], fold.gate[tok[q]], c, N, be, sum[q]);
+            } else {
+                store_out<FIRST>(outp, tl.row0 + lr0 + q, c, N, be, sum[q]);
+            }
         }
     }
 }

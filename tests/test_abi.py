@@ -161,3 +161,42 @@ def test_noalloc_entry_point_refuses_before_any_gpu_call():
     assert status(big) == moe.MOE_ERR_WORKSPACE
     # decoder steps of the NLLB-shaped layer fit
     assert moe.moe_workspace_bytes(shape(T=32, d_model=2048, d_ff=8192, E=128, k=2)) < moe.moe_noalloc_max_workspace()
+
+
+def test_tune_alpha_matches_the_oracle():
+    """Host arithmetic of the alpha auto-tuning step (Section 3.3, after Eq. 6) against the oracle: the hand-worked
+    cases, random inputs, and the refusals."""
+    import json
+
+    import numpy as np
+
+    from oracle import moe_oracle as orc
+    with open(os.path.join(ROOT, "tests", "golden", "alpha_tuning_examples.json")) as fh:
+        for c in json.load(fh)["cases"]:
+            a, best = moe.moe_tune_alpha(c["alpha"], c["bw_a"], c["bw_b"], c["activated"], c["times"])
+            assert best == c["best"] and abs(a - c["alpha_new"]) <= 1e-15 * max(1.0, c["alpha_new"]), c
+    rng = np.random.default_rng(23)
+    for _ in range(200):
+        B, C = int(rng.integers(1, 7)), int(rng.integers(1, 5))
+        t = rng.uniform(0.5, 3.0, (B, C))
+        if rng.integers(0, 3) == 0:
+            t[:, rng.integers(0, C)] = t[:, 0]                # equal totals happen
+        act = rng.integers(0, 130, B)
+        alpha, a, b = float(rng.uniform(0, 3)), float(rng.uniform(1, 100)), float(rng.uniform(0, 1000))
+        got = moe.moe_tune_alpha(alpha, a, b, act, t)
+        want = orc.tune_alpha(alpha, a, b, act, t)
+        assert got[1] == want[1] and got[0] == want[0], (got, want)      # same operations in the same order
+    lib = moe.load()
+    act = (ctypes.c_int32 * 2)(3, 4)
+    t = (ctypes.c_double * 4)(1.0, 2.0, 3.0, 4.0)
+    out = ctypes.c_double(-1.0)
+
+    def status(alpha=1.0, bw_a=1.0, bw_b=1.0, nb=2, a=act, nc=2, tt=t):
+        return lib.moe_tune_alpha(alpha, bw_a, bw_b, nb, a, nc, tt, ctypes.addressof(out), None)
+
+    assert status() == moe.MOE_OK and out.value == 1.0        # totals (4, 6): offset 0
+    assert status(nb=0) == moe.MOE_ERR_INVALID_ARG and status(nc=0) == moe.MOE_ERR_INVALID_ARG
+    assert status(a=None) == moe.MOE_ERR_INVALID_ARG and status(tt=None) == moe.MOE_ERR_INVALID_ARG
+    assert status(bw_a=0.0) == moe.MOE_ERR_INVALID_ARG and status(alpha=float("nan")) == moe.MOE_ERR_INVALID_ARG
+    assert status(tt=(ctypes.c_double * 4)(1.0, 0.0, 3.0, 4.0)) == moe.MOE_ERR_INVALID_ARG
+    assert status(a=(ctypes.c_int32 * 2)(3, -1)) == moe.MOE_ERR_INVALID_ARG

@@ -594,6 +594,62 @@ def test_select_hot(gpu_lib, name):
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------------------ alpha auto-tuning
+@pytest.mark.gpu
+def test_tune_alpha_on_measured_candidates(gpu_lib):
+    """Section 3.3, after Eq. 6: profiled runs of a few past batches with H, H + 1 and H + 2 hot experts pick the
+    candidate and from it the new alpha.  The layer runs each candidate's hot share (moe_layer_forward with H on
+    the device), HIP events time them, and moe_tune_alpha's choice from the measured times must be the oracle's
+    on the same numbers: the offset with the smallest total, and the alpha it implies; Eq. 6 at the new alpha
+    then yields the chosen count on a batch of the mean size."""
+    from dataclasses import replace
+
+    from paper_2405_18832_amd.device_layer import DeviceLayer
+    say("[case] moe_tune_alpha on measured candidates")
+    base = wl.MoEConfig("alpha_tuning", T=1024, d_model=256, d_ff=1024, E=48, k=2, dtype="bf16", renormalize=True,
+                        seed=61, zipf_s=1.0, gate_std=0.06)
+    alpha, bw_a, bw_b, C = 1.0, 64.0, 192.0, 3
+    experts = {}
+
+    def expert(e):
+        if e not in experts:
+            experts[e] = wl.make_expert(base, e)
+        return experts[e]
+
+    wg, b = wl.make_gate(base)
+    activated, times = [], []
+    for batch in range(3):                                  # three past batches: other tokens, same layer
+        cfg = replace(base, seed=base.seed + 100 * batch)
+        x = wl.make_activations(cfg)
+        r = orc.route(x, wg, b, cfg.k, cfg.renormalize)
+        H0 = orc.hot_expert_count(r["counts"], alpha, bw_a, bw_b)
+        activated.append(orc.activated_experts(r["counts"]))
+        L = DeviceLayer(base, x, wg, b, expert)
+        row = []
+        for c in range(C):
+            for _ in range(3):
+                L.forward(H=H0 + c)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                L.forward(H=H0 + c, debug=True)
+            e1.record()
+            torch.cuda.synchronize()
+            row.append(e0.elapsed_time(e1) / 20.0)
+            assert int(L.hot_mask.sum().item()) == min(H0 + c, cfg.E)
+        times.append(row)
+        del L
+    say(f"[alpha] activated {activated}, times (ms) {np.round(np.array(times), 4).tolist()}")
+    got = gpu_lib.moe_tune_alpha(alpha, bw_a, bw_b, activated, times)
+    want = orc.tune_alpha(alpha, bw_a, bw_b, activated, times)
+    assert got == want
+    tot = np.array(times).sum(axis=0)
+    assert got[1] == int(np.argmin(tot))
+    mean_counts = [1] * int(round(np.mean(activated))) + [0] * (base.E - int(round(np.mean(activated))))
+    assert orc.hot_expert_count(mean_counts, got[0], bw_a, bw_b) >= orc.hot_expert_count(mean_counts, alpha, bw_a, bw_b) + got[1] - 1
+    say(f"[alpha] chosen offset {got[1]}, alpha {alpha} -> {got[0]:.4f}")
+
+
 # ------------------------------------------------------------------------------ on-demand expert fetch
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", ["many_experts", "ragged_bf16"])

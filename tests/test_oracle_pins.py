@@ -434,3 +434,38 @@ def test_error_statistics_properties():
     z = np.zeros((1, 4))
     assert np.allclose(orc.rel_error_rows(z + 0.25, z), 0.25) and np.allclose(orc.row_error_norms(z + 0.25, z), 0.5)
     assert np.allclose(orc.rel_error(z + 0.25, z), 0.25)
+
+
+# ---------------------------------------------------------------- alpha auto-tuning (Section 3.3, after Eq. 6)
+def test_tune_alpha_hand_worked_and_properties():
+    with open(os.path.join(GOLD, "alpha_tuning_examples.json")) as fh:
+        cases = json.load(fh)["cases"]
+    for c in cases:
+        a, best = orc.tune_alpha(c["alpha"], c["bw_a"], c["bw_b"], c["activated"], c["times"])
+        assert best == c["best"], c
+        assert abs(a - c["alpha_new"]) <= 1e-15 * max(1.0, abs(c["alpha_new"])), c
+    rng = np.random.default_rng(17)
+    for _ in range(100):
+        B, C = int(rng.integers(1, 6)), int(rng.integers(1, 4))
+        t = rng.uniform(1.0, 2.0, (B, C))
+        act = rng.integers(1, 120, B)
+        alpha, a, b = float(rng.uniform(0.2, 3)), float(rng.uniform(1, 100)), float(rng.uniform(1, 1000))
+        an, best = orc.tune_alpha(alpha, a, b, act, t)
+        # the chosen offset has the smallest total; among equal totals the smallest offset
+        tot = t.sum(axis=0)
+        assert tot[best] <= tot.min() * (1 + 1e-12) and best == int(np.argmin(tot))
+        # the meaning of the new alpha: Eq. 6's real-valued H of the mean batch rises by exactly the offset
+        rho, mean = a / (a + b), act.mean()
+        assert abs(an * rho * mean - (alpha * rho * mean + best)) <= 1e-9 * (1 + alpha * rho * mean + best)
+        # neither the unit of the times nor the order of the batches matters
+        p = rng.permutation(B)
+        an2, best2 = orc.tune_alpha(alpha, a, b, act[p], 1000.0 * t[p])
+        assert best2 == best and abs(an2 - an) <= 1e-12 * an
+        # candidate 0 best -> unchanged
+        t0 = t.copy()
+        t0[:, 0] = 0.5
+        assert orc.tune_alpha(alpha, a, b, act, t0) == (alpha, 0)
+    # a larger offset moves the integer H of Eq. 6 up by about that much on a batch of the mean size
+    an, best = orc.tune_alpha(1.0, 64.0, 512.0, [45, 45], [[3.0, 2.0, 1.0], [3.0, 2.0, 1.0]])
+    assert best == 2
+    assert orc.hot_expert_count([1] * 45, an, 64.0, 512.0) == orc.hot_expert_count([1] * 45, 1.0, 64.0, 512.0) + 2
