@@ -408,9 +408,6 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
                                                          int act_kmajor, int rows_in_lds,
                                                          const float* __restrict__ bias, const FoldOut fold) {
     extern __shared__ __attribute__((aligned(16))) unsigned char tok_lds[];
-    // first the rows that the tiled kernel before this one left as partial tiles (large experts; no
-    // overlap with the rows of the small experts below)
-    if (partials != nullptr) finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, bias, fold);
     constexpr int NGB = 4 / KSPLIT;   // n-groups (of 64 columns) per block
     __shared__ f32x4 red[KSPLIT > 1 ? (KSPLIT - 1) * NGB * 4 * TFMAX * 64 : 1];
     const int wave = threadIdx.x >> 6;
@@ -435,6 +432,20 @@ __global__ __launch_bounds__(256) void ffn_stream_kernel(const uint16_t* __restr
     // fetched into that L2 once instead of into all eight.
     const int pb = (stride % 8 == 0) ? static_cast<int>(blockIdx.x & 7) * (stride >> 3) + static_cast<int>(blockIdx.x >> 3)
                                      : static_cast<int>(blockIdx.x);
+    // First the rows that the tiled kernel before this one left as partial tiles (large experts; no overlap
+    // with the rows of the small experts below).  When at least a quarter of the blocks have no streaming unit
+    // they do it, side by side with the others' streaming; else everybody does, before streaming.
+    if (partials != nullptr) {
+        const int idle = stride - nbu;                    // blocks with pb >= nbu have no unit (balance is off here)
+        if (idle * 4 >= stride) {
+            if (pb >= nbu)
+                finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, bias, fold,
+                                                pb - nbu, idle);
+        } else {
+            finish_split_units<FIRST, FOLD>(big_tiles, ntiles_p[1], partials, outp, N, K >> 5, tile_grid, bias, fold,
+                                            static_cast<int>(blockIdx.x), static_cast<int>(gridDim.x));
+        }
+    }
     for (int base = 0; base < nbu; base += stride) {
         const int bu = base + pb;
         if (bu >= nbu) break;                             // block-uniform
@@ -649,6 +660,12 @@ hipError_t configure_ffn_kernels(int dev) {
 // split at all when that still leaves two units for every CU (`tiles_expected`: about how many tiles there
 // will be): a wavefront then streams its whole contraction in one go, with the rows read from LDS
 // (measured on the decode preset, first product: 285 -> 257 us).
+#ifndef MOE_KS4_MIN_STEPS
+#define MOE_KS4_MIN_STEPS 96
+#endif
+#ifndef MOE_KS2_MIN_STEPS
+#define MOE_KS2_MIN_STEPS 32     // (48 before: with 32 the first product of a d_model = 1024 layer with few small
+#endif                           // experts spreads over twice the blocks: 21.7 -> 16.0 us on the Switch-large preset)
 static int pick_ksplit(int K, int N, int tfmax, long tiles_expected) {
     const int steps = K / 32;
     if (tfmax <= 2) {
@@ -656,7 +673,7 @@ static int pick_ksplit(int K, int N, int tfmax, long tiles_expected) {
         const long units_unsplit = tiles_expected * ((N / 64 + 3) / 4);
         if (rows_fit && units_unsplit >= 2L * device_cu_count()) return 1;
     }
-    const int s4 = tfmax <= 2 ? 64 : 96, s2 = tfmax <= 2 ? 32 : 48;
+    const int s4 = tfmax <= 2 ? 64 : MOE_KS4_MIN_STEPS, s2 = tfmax <= 2 ? 32 : MOE_KS2_MIN_STEPS;
     if (steps >= s4) return 4;
     if (steps >= s2) return 2;
     return 1;

@@ -212,7 +212,8 @@ __device__ __forceinline__ void store_folded_block32(uint16_t* out, int t, float
 }
 
 // Adds up the partial tiles that a tiled product of grid G left behind and writes the output rows.
-// Called by every thread of every block of the following kernel.  A wavefront takes four consecutive rows of a
+// Called by every thread of `nblocks` blocks of the following kernel, `block` being the caller's rank among
+// them.  A wavefront takes four consecutive rows of a
 // cut unit at a time (a row of a unit is 256 columns: 4 per lane): what is the same for the whole row -- the unit,
 // its row tile, for a folded output the row's token and gate weight -- is looked up once per wavefront, and the
 // 4 x split loads of partial sums go out together (one row at a time, with a lookup per element, the pass was a
@@ -221,7 +222,8 @@ template <int FIRST, bool FOLD>
 __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_tiles, int ntiles_big,
                                                    const float* __restrict__ partials, void* __restrict__ outp,
                                                    int N, int kblk, int G,
-                                                   const float* __restrict__ bias, const FoldOut fold) {
+                                                   const float* __restrict__ bias, const FoldOut fold, int block,
+                                                   int nblocks) {
     if (ntiles_big <= 0 || partials == nullptr) return;
     const TileSchedule s = tile_schedule(ntiles_big, N, kblk, G, true);
     if (s.split < 2) return;
@@ -230,8 +232,8 @@ __device__ __forceinline__ void finish_split_units(const Tile* __restrict__ big_
     constexpr size_t kTileFloats = static_cast<size_t>(kBigTileRows) * kTileCols;
     const int lane = threadIdx.x & 63;
     const int waves_per_block = blockDim.x >> 6;
-    const int first = __builtin_amdgcn_readfirstlane(static_cast<int>(blockIdx.x) * waves_per_block + (threadIdx.x >> 6));
-    const int nwaves = static_cast<int>(gridDim.x) * waves_per_block;
+    const int first = __builtin_amdgcn_readfirstlane(block * waves_per_block + static_cast<int>(threadIdx.x >> 6));
+    const int nwaves = nblocks * waves_per_block;
     const int total = s.R * kGroups;
     for (int i = first; i < total; i += nwaves) {              // wave-uniform
         const int ru = i / kGroups, lr0 = (i % kGroups) * kRowsAtOnce;
