@@ -77,13 +77,15 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "70eaa5058c3cc82c", "ffn_tile.hip": "d6e05b7ff0696246",
-                   "tile_schedule.hpp": "cfb38ed553932c2c", "common.hpp": "8de102ccc6a3c46a"}
+TRAFFIC_SOURCES = {"ffn.hip": "543aebfd5fdd7559", "ffn_tile.hip": "10da39e038cc7ea1",
+                   "tile_schedule.hpp": "51b4bf8f49c878b2", "common.hpp": "36b9d4fd168e4585"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316508645, ("switch_base", "stream_w2"): 320281156,
-    ("nllb_decode", "stream_w1"): 1643649720, ("nllb_decode", "stream_w2"): 1645597904,
-    ("nllb_prefill_skew", "stream_w1"): 1158802682, ("nllb_prefill_skew", "stream_w2"): 1152661958,
-    ("nllb_prefill_skew", "tile_w1"): 2503146561, ("nllb_prefill_skew", "tile_w2"): 2212283334,
+    ("switch_base", "stream_w1"): 316565037, ("switch_base", "stream_w2"): 320294004,
+    ("switch_large_skew", "stream_w1"): 68332429, ("switch_large_skew", "stream_w2"): 141341785,
+    ("switch_large_skew", "tile_w1"): 90825623, ("switch_large_skew", "tile_w2"): 217135575,
+    ("nllb_decode", "stream_w1"): 1643645065, ("nllb_decode", "stream_w2"): 1645589074,
+    ("nllb_prefill_skew", "stream_w1"): 1158885787, ("nllb_prefill_skew", "stream_w2"): 1152787096,
+    ("nllb_prefill_skew", "tile_w1"): 2487368754, ("nllb_prefill_skew", "tile_w2"): 2215495788,
 }
 
 

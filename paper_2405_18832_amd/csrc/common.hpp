@@ -111,7 +111,9 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 // outstanding LDS reads (as long as a copy is in flight, which here is always), and the loops that
 // use it depend on waiting only for the oldest ones.  The copies are counted by vmcnt; the code waits for
 // them explicitly, and orders them against LDS reads with barriers.  M0 is not live across statements
-// in compiled code for this target (the compiler sets it right before each use of its own).
+// in compiled code for this target (the compiler sets it right before each use of its own); it cannot be named
+// in the clobber list, the compiler rejects reserved registers there ("may not be preserved across the asm
+// statement"), so that property is what the statement relies on.
 __device__ __forceinline__ void copy16_to_lds(const void* src, uint32_t lds_base) {
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base);
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory");

@@ -724,6 +724,51 @@ def test_layer_forward_in_a_graph(gpu_lib, name):
         torch.cuda.synchronize()
 
 
+CAPTURE_FIRST = r"""
+import sys
+import numpy as np
+import torch
+import workloads as wl
+import paper_2405_18832_amd as moe
+from paper_2405_18832_amd.device_layer import DeviceLayer
+moe.load()
+moe.moe_init()                               # all one-time runtime calls happen here, before the capture
+cfg = wl.MoEConfig("capture_first", T=300, d_model=128, d_ff=512, E=12, k=2, dtype="bf16", renormalize=True,
+                   seed=71, zipf_s=1.0, gate_std=0.3)
+layer = wl.make_layer(cfg)
+L = DeviceLayer(cfg, layer.x, layer.w_gate, layer.b_gate, layer.expert)
+torch.cuda.synchronize()
+side = torch.cuda.Stream()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g, stream=side):       # the library's first layer call of this process
+    L.forward()
+torch.cuda.synchronize()
+L.out.zero_()
+g.replay()
+torch.cuda.synchronize()
+got = L.out.clone()
+L.out.zero_()
+L.forward()
+torch.cuda.synchronize()
+assert torch.isfinite(got.float()).all() and got.abs().sum() > 0
+assert torch.equal(got.view(torch.int16), L.out.view(torch.int16))
+print("capture-first ok")
+"""
+
+
+@pytest.mark.gpu
+def test_first_layer_call_inside_a_capture(gpu_lib):
+    """moe_init makes every one-time call into the runtime (dynamic-LDS limits, occupancy), so that the very
+    first layer call of a process can be recorded into a graph: checked in a fresh process."""
+    import os
+    import subprocess
+    say("[case] first call of a process inside a graph capture")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", CAPTURE_FIRST], cwd=root, capture_output=True, text=True, timeout=300)
+    say(r.stdout[-500:], r.stderr[-1500:])
+    assert r.returncode == 0 and "capture-first ok" in r.stdout
+
+
 # ------------------------------------------------------------------------------ degenerate inputs
 def test_no_tokens_and_empty_mask(gpu_lib):
     from paper_2405_18832_amd.device_layer import DeviceLayer
