@@ -21,7 +21,13 @@ a hand-derived worked example, invariants and metamorphic relations (see
 tests).  The gate-weighting rule (probability of the chosen expert, optionally
 renormalised over the chosen k) is a reading of "outputs are combined"
 (Section 2.1), which the paper leaves open: in that sense `gate_weights` is
-"parity unpinned" with respect to the paper's text.
+"parity unpinned" with respect to the paper's text.  `activation_movement`
+(Eq. 2) is a one-line formula for which the paper prints no value: its test
+can only restate it and check its ratio to Eq. 1 (whose Table 2 sizes are
+pinned), so it is "parity unpinned" as well.  `tune_alpha` is a reading of
+the paragraph after Eq. 6 (the paper does not say how the best candidate
+becomes a new alpha): "parity unpinned" with respect to the paper, its
+arithmetic pinned by hand-worked examples.
 
 Conventions: T tokens, d = d_model, f = d_ff, E experts, k experts per token,
 A = T*k assignments, flat assignment id a = t*k + j (slot j = 0 is the best

@@ -172,10 +172,8 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
 #pragma unroll
         for (int q = 0; q < 4; ++q) copy_piece(st, q);
     };
-    // Point the copies at a unit and start its first stages.  Every wavefront must be done reading the
-    // ring (its MFMAs have consumed the last stage): a bare barrier, so that output stores still in flight
-    // need not complete first.
-    auto start_unit = [&](const Unit& w) {
+    // Point the copies at a unit's first k-step.
+    auto point_copies_at = [&](const Unit& w) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             int row = w.tl.row0 + min((2 * wave + i) * 16 + r, w.tl.rows - 1);
@@ -186,10 +184,19 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
             const int nb = min(w.nt * 16 + 2 * wave + i, nblk - 1);
             brow[i] = wpk + ((static_cast<size_t>(w.tl.expert) * nblk + nb) * kblk + w.kb0) * 512 + lane * 8;
         }
+    };
+    // The ring runs on across units: `slot` is the slot of the current unit's current stage, and the first
+    // stage of the next unit follows the last stage of this one.
+    int slot = 0;
+    // Start a unit from a standstill: its first stages into the slots from `slot` on.  Every wavefront must be
+    // done reading the ring (its MFMAs have consumed the last stage): a bare barrier, so that output stores
+    // still in flight need not complete first.
+    auto start_unit = [&](const Unit& w) {
+        point_copies_at(w);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
         for (int sidx = 0; sidx < kAhead; ++sidx)
-            if (sidx < w.nk) stage_in(sidx);
+            if (sidx < w.nk) stage_in((slot + sidx) % kStages);
     };
 
     const int wave_w = kOperandBytes + (wn * 4 * 64 + lane) * 16, wave_x = (wm * 8 * 64 + lane) * 16;
@@ -202,6 +209,10 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         const bool next_known = it + 1 < sch.rounds;
         Unit nxt;
         if (next_known) nxt = unit_at(it + 1);
+        // The next unit's first stages go out during this unit's last iterations, in the slots that fall free
+        // there, when the unit is known by then, needs no row lookups (a vector load here would make the
+        // compiler wait for every copy in flight) and both units are at least as long as the ring is deep.
+        const bool ahead = next_known && nxt.valid && rowmap == nullptr && nk >= kAhead && nxt.nk >= kAhead;
         f32x4 acc[4][8];
 #pragma unroll
         for (int nf = 0; nf < 4; ++nf)
@@ -218,23 +229,27 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         // after a global-to-LDS copy was issued the compiler waits for all outstanding LDS reads, not
         // only the needed ones: here that is at the first MFMA, when only old reads are outstanding.)
         // `steady`: stage j + kAhead exists, so nothing in the iteration is conditional.
-        int slot = 0;                                      // ring slot of stage j
         auto iterate = [&](auto cbuf, auto steady, int j) {
             constexpr int C = decltype(cbuf)::value;
             constexpr bool STEADY = decltype(steady)::value;
             const int slot_next = slot + 1 == kStages ? 0 : slot + 1;
             const int slot_free = slot == 0 ? kStages - 1 : slot - 1;          // held stage j - 1
-            const unsigned char* cur = smem + slot * kStageBytes;
-            const unsigned char* nxt = smem + slot_next * kStageBytes;
+            const unsigned char* st_cur = smem + slot * kStageBytes;
+            const unsigned char* st_nxt = smem + slot_next * kStageBytes;
             const bool more = STEADY || j + 1 < nk;        // block-uniform
             if (more) {
-                // stages j + 2 ... j + kAhead - 1 (as far as they exist) may stay in flight
-                wait_copies(STEADY ? kAhead - 2 : min(j + kAhead - 1, nk - 1) - (j + 1));
+                // stages j + 2 ... j + kAhead - 1 (as far as they exist) may stay in flight; with the next unit's
+                // stages behind them that is always kAhead - 2 stages' worth
+                wait_copies((STEADY || ahead) ? kAhead - 2 : min(j + kAhead - 1, nk - 1) - (j + 1));
                 asm volatile("s_barrier" ::: "memory");
+            } else if (ahead) {
+                asm volatile("s_barrier" ::: "memory");   // the slot of stage j - 1 is about to be refilled
             }
+            // from here on the stages that go out are the next unit's
+            if (!STEADY && ahead && j + kAhead == nk) point_copies_at(nxt);
             // the four copies of stage j + kAhead are issued between the first MFMAs, whose execution
             // covers the scalar and address arithmetic of the copies
-            const bool refill = more && (STEADY || j + kAhead < nk);
+            const bool refill = (more && (STEADY || j + kAhead < nk)) || (!STEADY && ahead && j + kAhead >= nk);
 #pragma unroll
             for (int nf = 0; nf < 4; ++nf) {
                 __builtin_amdgcn_sched_barrier(0);
@@ -244,19 +259,19 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
                 if (refill) copy_piece(slot_free, nf);
             }
             __builtin_amdgcn_sched_barrier(0);
-            lds_read_x(fr.x[3], cur + wave_x, 3);
+            lds_read_x(fr.x[3], st_cur + wave_x, 3);
             if (more) {
-                lds_read_w(fr.w[C ^ 1], nxt + wave_w);
-                lds_read_x(fr.x[0], nxt + wave_x, 0);
+                lds_read_w(fr.w[C ^ 1], st_nxt + wave_w);
+                lds_read_x(fr.x[0], st_nxt + wave_x, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
             mfma_pair<1>(fr.w[C], fr.x[1], acc);
             __builtin_amdgcn_sched_barrier(0);
-            if (more) lds_read_x(fr.x[1], nxt + wave_x, 1);
+            if (more) lds_read_x(fr.x[1], st_nxt + wave_x, 1);
             __builtin_amdgcn_sched_barrier(0);
             mfma_pair<2>(fr.w[C], fr.x[2], acc);
             __builtin_amdgcn_sched_barrier(0);
-            if (more) lds_read_x(fr.x[2], nxt + wave_x, 2);
+            if (more) lds_read_x(fr.x[2], st_nxt + wave_x, 2);
             __builtin_amdgcn_sched_barrier(0);
             mfma_pair<3>(fr.w[C], fr.x[3], acc);
             __builtin_amdgcn_sched_barrier(0);
@@ -268,10 +283,10 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         // number of operations stays outstanding and the copies complete in order.
         wait_copies(min(kAhead, nk) - 1);                  // stage 0 has landed ...
         asm volatile("s_barrier" ::: "memory");           // ... for every wavefront
-        lds_read_w(fr.w[0], smem + wave_w);
-        lds_read_x(fr.x[0], smem + wave_x, 0);
-        lds_read_x(fr.x[1], smem + wave_x, 1);
-        lds_read_x(fr.x[2], smem + wave_x, 2);
+        lds_read_w(fr.w[0], smem + slot * kStageBytes + wave_w);
+        lds_read_x(fr.x[0], smem + slot * kStageBytes + wave_x, 0);
+        lds_read_x(fr.x[1], smem + slot * kStageBytes + wave_x, 1);
+        lds_read_x(fr.x[2], smem + slot * kStageBytes + wave_x, 2);
         int j = 0;
         for (; j + 1 + kAhead < nk; j += 2) {
             iterate(std::integral_constant<int, 0>{}, std::true_type{}, j);
@@ -287,7 +302,7 @@ __global__ __launch_bounds__(512) void ffn_tile_kernel(const uint16_t* __restric
         // The next unit's first copies go out before this unit's output is stored: the copies' latency and
         // the stores overlap, and the load of the next tile's descriptor does not wait behind the stores.
         if (!next_known) nxt = unit_at(it + 1);
-        if (nxt.valid) start_unit(nxt);
+        if (nxt.valid && !ahead) start_unit(nxt);
 
         // Lane holds 4 consecutive columns of one row per accumulator.
         if (cur.nparts > 1) {
