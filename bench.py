@@ -77,15 +77,15 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "543aebfd5fdd7559", "ffn_tile.hip": "10da39e038cc7ea1",
-                   "tile_schedule.hpp": "51b4bf8f49c878b2", "common.hpp": "36b9d4fd168e4585"}
+TRAFFIC_SOURCES = {"ffn.hip": "543aebfd5fdd7559", "ffn_tile.hip": "436f9bad48effd6a",
+                   "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "36b9d4fd168e4585"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316565037, ("switch_base", "stream_w2"): 320294004,
-    ("switch_large_skew", "stream_w1"): 68332429, ("switch_large_skew", "stream_w2"): 141341785,
-    ("switch_large_skew", "tile_w1"): 90825623, ("switch_large_skew", "tile_w2"): 217135575,
-    ("nllb_decode", "stream_w1"): 1643645065, ("nllb_decode", "stream_w2"): 1645589074,
-    ("nllb_prefill_skew", "stream_w1"): 1158885787, ("nllb_prefill_skew", "stream_w2"): 1152787096,
-    ("nllb_prefill_skew", "tile_w1"): 2487368754, ("nllb_prefill_skew", "tile_w2"): 2215495788,
+    ("switch_base", "stream_w1"): 316539802, ("switch_base", "stream_w2"): 320284463,
+    ("switch_large_skew", "stream_w1"): 68332531, ("switch_large_skew", "stream_w2"): 141341072,
+    ("switch_large_skew", "tile_w1"): 90877809, ("switch_large_skew", "tile_w2"): 133077923,
+    ("nllb_decode", "stream_w1"): 1643644656, ("nllb_decode", "stream_w2"): 1645617501,
+    ("nllb_prefill_skew", "stream_w1"): 1158892024, ("nllb_prefill_skew", "stream_w2"): 1152738421,
+    ("nllb_prefill_skew", "tile_w1"): 2517733563, ("nllb_prefill_skew", "tile_w2"): 2209532819,
 }
 
 
