@@ -72,30 +72,35 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const V* __restrict__ 
 }
 
 // gather into the blocked layout of the products' row operand (h_index): element (p, c) of xk is
-// x[tokmap[p]][c] (tokmap may be NULL: identity).  One thread per 16 bytes of the destination, which is written
-// contiguously (the rows past A of the last row block stay unwritten); every token row is read in 64-byte pieces.
+// x[tokmap[p]][c] (tokmap may be NULL: identity).  One thread per 16 bytes.  Eight consecutive threads take the
+// 128 bytes of one row that make up two k-steps, so every line of a token row is fetched whole and once (with
+// one k-step per group of four threads the two halves of a line were read by blocks on different XCDs, and the
+// kernel fetched twice its input); a wavefront then writes two runs of 512 contiguous bytes, the same eight rows
+// of both k-steps.  The rows past A of the last row block stay unwritten.
 __global__ __launch_bounds__(256) void gather_kmajor_kernel(const uint4* __restrict__ x,
                                                             const int32_t* __restrict__ tokmap,
                                                             uint4* __restrict__ xk, int A, int T, int row_vecs,
                                                             size_t total) {
     const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    // destination order: [row block][k-step][row in block][4 pieces of 16 bytes]
-    const int c = static_cast<int>(i & 3);
-    const int r = static_cast<int>((i >> 2) & (kRowBlock - 1));
-    const size_t bk = i >> 10;                          // row block * ksteps + kb
-    const int ksteps = row_vecs >> 2;
-    const int kb = static_cast<int>(bk % ksteps);
-    const size_t p = (bk / ksteps) * kRowBlock + r;
-    if (p >= static_cast<size_t>(A)) return;
+    // thread order: [row block][pair of k-steps][row in block][8 pieces of 16 bytes: 4 of each k-step]
+    const int piece = static_cast<int>(i & 7);
+    const int r = static_cast<int>((i >> 3) & (kRowBlock - 1));
+    const size_t bk = i >> 11;                          // row block * kpairs + pair
+    const int ksteps = row_vecs >> 2, kpairs = (ksteps + 1) >> 1;
+    const int kb = static_cast<int>(bk % kpairs) * 2 + (piece >> 2), c = piece & 3;
+    const size_t rb = bk / kpairs;
+    const size_t p = rb * kRowBlock + r;
+    if (p >= static_cast<size_t>(A) || kb >= ksteps) return;
     const int t = tokmap ? min(max(tokmap[p], 0), T - 1) : static_cast<int>(p);   // no map: x already has the A rows in order
-    xk[i] = x[static_cast<size_t>(t) * row_vecs + kb * 4 + c];
+    xk[((rb * ksteps + kb) * kRowBlock + r) * 4 + c] = x[static_cast<size_t>(t) * row_vecs + kb * 4 + c];
 }
 
 hipError_t launch_gather_kmajor(const moe_shape& s, const void* x, const int32_t* tokmap, void* xk, hipStream_t st) {
     const int A = s.T * s.k;
     const size_t Ab = (static_cast<size_t>(A) + kRowBlock - 1) / kRowBlock * kRowBlock;
-    const size_t total = Ab * s.d_model / 8;                          // bf16: 8 elements per 16 bytes
+    const size_t ksteps = static_cast<size_t>(s.d_model) / 32;
+    const size_t total = Ab * ((ksteps + 1) / 2) * 8;                 // one thread per 16 bytes, k-steps in pairs
     hipLaunchKernelGGL(gather_kmajor_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
                        static_cast<const uint4*>(x), tokmap, static_cast<uint4*>(xk), A, s.T, s.d_model / 8, total);
     return hipGetLastError();
