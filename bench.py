@@ -114,6 +114,47 @@ def config_of(name: str):
             else wl.CONFIGS.get(name) or wl.EXTRA_CONFIGS[name])
 
 
+def hot_cold_shares_context(L, H: int, steps: int) -> dict:
+    """Context, not the metric: the paper's two workflows side by side (Section 3.3).  The hot share (top-H mask) and
+    the cold share (its complement) as two moe_layer_forward calls, each with its own workspace and output, once on
+    two streams at the same time and once back to back on one stream, against the single full call."""
+    import torch
+
+    import paper_2405_18832_amd as moe
+    L.route(H=H)
+    torch.cuda.synchronize()
+    hot = L.hot_mask.clone()
+    cold = (1 - hot).to(torch.uint8)
+    ws2, out2 = torch.empty_like(L.ws), torch.empty_like(L.out)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    cur = torch.cuda.current_stream()
+
+    def call(mask, out, ws, stream, i):
+        w1, w2 = L.weight_copies[i % len(L.weight_copies)]
+        moe.moe_layer_forward(L.shape, L.x, L.w_gate, L.b_gate, w1, w2, mask, -1, out, ws=ws, stream=stream.cuda_stream)
+
+    def timed(step):
+        for i in range(2):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e3
+
+    def both_streams(i):
+        call(hot, L.out, L.ws, sa, i)
+        call(cold, out2, ws2, sb, i)
+
+    def one_stream(i):
+        call(hot, L.out, L.ws, cur, i)
+        call(cold, out2, ws2, cur, i)
+
+    return {"hot_experts": int(hot.sum().item()), "two_streams_ms": timed(both_streams),
+            "one_stream_ms": timed(one_stream), "full_call_ms": timed(lambda i: L.forward(copy=i)), "steps": steps}
+
+
 def library_gemm_context(M: int, d: int, f: int) -> dict:
     """Context, not a target: the ROCm BLAS library's dense bf16 GEMM (through torch.matmul) on the shapes of the
     two products of the large experts taken together, M rows, with normal random operands (the second product's
@@ -369,12 +410,18 @@ def measure(name: str, share: str, K: int, W: int, copies_arg: int = 0, cpu_base
             f"hidden activation in bf16: {err_s if err_s is None else format(err_s, '.3e')}")
 
     ctx = None
+    if cpu_baseline and cfg.H is not None and not hot:
+        ctx = {"hot_cold_shares": hot_cold_shares_context(L, cfg.H, K)}
+        hc = ctx["hot_cold_shares"]
+        log(f"[bench] context: hot share ({hc['hot_experts']} experts) and cold share as two calls: "
+            f"{hc['two_streams_ms']:.3f} ms on two streams at once, {hc['one_stream_ms']:.3f} ms back to back on one, "
+            f"{hc['full_call_ms']:.3f} ms for the one full call")
     if cpu_baseline and rows_b > 0 and roof is not None and roof["bound"] == "mfma":
         del L
         L = None
         gc.collect()
         torch.cuda.empty_cache()
-        ctx = {"library_gemm": library_gemm_context(rows_b, d, f)}
+        ctx = dict(ctx or {}, library_gemm=library_gemm_context(rows_b, d, f))
         log("[bench] context: library bf16 GEMM on the large experts' rows taken together: "
             + ", ".join(f"{k_} {v['us']:.0f} us = {v['tflops']:.0f} TFLOP/s ({v['frac_of_peak']:.3f} of peak)"
                         for k_, v in ctx["library_gemm"].items()))

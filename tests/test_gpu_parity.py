@@ -726,6 +726,47 @@ def test_layer_forward_in_a_graph(gpu_lib, name):
         torch.cuda.synchronize()
 
 
+# The paper's two workflows side by side (Section 3.3: the hot experts on one device, the cold ones on the
+# other, concurrently; the outputs meet in one combine).  On one GPU that is two calls, each with its share's
+# mask, its own workspace and output, on two streams at once.
+@pytest.mark.parametrize("name", ["switch_large_skew", "tokens_8k", "nllb_prefill_skew"])
+def test_hot_and_cold_shares_on_two_streams(gpu_lib, name):
+    cfg = CFG(name)
+    say(f"[case] hot and cold shares on two streams, {name}")
+    r = oracle_route(name)
+    L = device_layer(gpu_lib, name)
+    H = cfg.H if cfg.H is not None else max(1, cfg.E // 3)
+    hot_np = orc.hot_mask_top_h(r["counts"], H).astype(np.uint8)
+    hot, cold = torch.from_numpy(hot_np).cuda(), torch.from_numpy(1 - hot_np).cuda()
+    # each share alone, one after the other on the current stream: what the concurrent calls must reproduce
+    alone = {}
+    for label, m in (("hot", hot), ("cold", cold)):
+        L.out.fill_(float("nan"))
+        L.forward(mask=m)
+        torch.cuda.synchronize()
+        alone[label] = L.out.clone()
+    ws2, out2 = torch.empty_like(L.ws), torch.empty_like(L.out)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        L.out.fill_(float("nan"))
+        out2.fill_(float("nan"))
+        torch.cuda.synchronize()
+        gpu_lib.moe_layer_forward(L.shape, L.x, L.w_gate, L.b_gate, L.w1, L.w2, hot, -1, L.out, ws=L.ws,
+                                  stream=sa.cuda_stream)
+        gpu_lib.moe_layer_forward(L.shape, L.x, L.w_gate, L.b_gate, L.w1, L.w2, cold, -1, out2, ws=ws2,
+                                  stream=sb.cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(L.out.view(torch.int16), alone["hot"].view(torch.int16)), f"hot share, repetition {rep}"
+        assert torch.equal(out2.view(torch.int16), alone["cold"].view(torch.int16)), f"cold share, repetition {rep}"
+    # the shares add up to the layer (each was rounded once; the bound of test_layer_forward)
+    L.forward()
+    torch.cuda.synchronize()
+    full = L.out.double().cpu().numpy()
+    a, b = alone["hot"].double().cpu().numpy(), alone["cold"].double().cpu().numpy()
+    row_rms = np.sqrt(np.mean(full ** 2, axis=1, keepdims=True))
+    assert np.all(np.abs(a + b - full) <= 2 * 2.0 ** -7 * (np.abs(a) + np.abs(b)) + 4e-3 * row_rms + 1e-30)
+
+
 CAPTURE_FIRST = r"""
 import sys
 import numpy as np
