@@ -80,12 +80,12 @@ class HipEvents:
 TRAFFIC_SOURCES = {"ffn.hip": "543aebfd5fdd7559", "ffn_tile.hip": "436f9bad48effd6a",
                    "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "36b9d4fd168e4585"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316539802, ("switch_base", "stream_w2"): 320284463,
-    ("switch_large_skew", "stream_w1"): 68332531, ("switch_large_skew", "stream_w2"): 141341072,
-    ("switch_large_skew", "tile_w1"): 90877809, ("switch_large_skew", "tile_w2"): 133077923,
-    ("nllb_decode", "stream_w1"): 1643644656, ("nllb_decode", "stream_w2"): 1645617501,
-    ("nllb_prefill_skew", "stream_w1"): 1158892024, ("nllb_prefill_skew", "stream_w2"): 1152738421,
-    ("nllb_prefill_skew", "tile_w1"): 2517733563, ("nllb_prefill_skew", "tile_w2"): 2209532819,
+    ("switch_base", "stream_w1"): 316557442, ("switch_base", "stream_w2"): 320294827,
+    ("switch_large_skew", "stream_w1"): 68330694, ("switch_large_skew", "stream_w2"): 141338560,
+    ("switch_large_skew", "tile_w1"): 90881720, ("switch_large_skew", "tile_w2"): 133076219,
+    ("nllb_decode", "stream_w1"): 1643660199, ("nllb_decode", "stream_w2"): 1645591119,
+    ("nllb_prefill_skew", "stream_w1"): 1158883740, ("nllb_prefill_skew", "stream_w2"): 1152749076,
+    ("nllb_prefill_skew", "tile_w1"): 2521680129, ("nllb_prefill_skew", "tile_w2"): 2210453140,
 }
 
 
