@@ -77,15 +77,15 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "543aebfd5fdd7559", "ffn_tile.hip": "436f9bad48effd6a",
-                   "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "36b9d4fd168e4585"}
+TRAFFIC_SOURCES = {"ffn.hip": "1011bc0bfcb93ea3", "ffn_tile.hip": "436f9bad48effd6a",
+                   "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "7306a852dfe63120"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316557442, ("switch_base", "stream_w2"): 320294827,
-    ("switch_large_skew", "stream_w1"): 68330694, ("switch_large_skew", "stream_w2"): 141338560,
-    ("switch_large_skew", "tile_w1"): 90881720, ("switch_large_skew", "tile_w2"): 133076219,
-    ("nllb_decode", "stream_w1"): 1643660199, ("nllb_decode", "stream_w2"): 1645591119,
-    ("nllb_prefill_skew", "stream_w1"): 1158883740, ("nllb_prefill_skew", "stream_w2"): 1152749076,
-    ("nllb_prefill_skew", "tile_w1"): 2521680129, ("nllb_prefill_skew", "tile_w2"): 2210453140,
+    ("switch_base", "stream_w1"): 316551992, ("switch_base", "stream_w2"): 320347734,
+    ("switch_large_skew", "stream_w1"): 68334158, ("switch_large_skew", "stream_w2"): 141349257,
+    ("switch_large_skew", "tile_w1"): 90880593, ("switch_large_skew", "tile_w2"): 133076322,
+    ("nllb_decode", "stream_w1"): 1643608457, ("nllb_decode", "stream_w2"): 1645583143,
+    ("nllb_prefill_skew", "stream_w1"): 913807298, ("nllb_prefill_skew", "stream_w2"): 972058691,
+    ("nllb_prefill_skew", "tile_w1"): 2569030516, ("nllb_prefill_skew", "tile_w2"): 2386985079,
 }
 
 
@@ -300,10 +300,11 @@ def measure(name: str, share: str, K: int, W: int, copies_arg: int = 0, cpu_base
               "combine_us": timed(lambda i: L.combine(mask=mask_t), reps)}
 
     # ---- roofline of the dominant kernel ---------------------------------------------------------
-    # Experts with >= 128 rows run in the LDS-tiled kernel, the others in the weight-streaming kernel
-    # (only when the layer has >= 128 tokens, else everything streams).
+    # Experts with at least `min_rows` rows run in the LDS-tiled kernel, the others in the weight-streaming
+    # kernel (the library says where the line is for these counts; 0: everything streams).
     d, f = cfg.d_model, cfg.d_ff
-    big = ran & (counts >= 128) if (cfg.dtype == "bf16" and cfg.T >= 128) else np.zeros_like(ran)
+    min_rows = moe.moe_tiled_kernel_min_rows(L.shape, [int(c) if r else 0 for c, r in zip(counts, ran)])
+    big = ran & (counts >= min_rows) if min_rows > 0 else np.zeros_like(ran)
     smalls = ran & ~big
     rows_s, rows_b = int(counts[smalls].sum()), int(counts[big].sum())
     wb_s, wb_b = int(smalls.sum()) * d * f * es, int(big.sum()) * d * f * es

@@ -240,6 +240,17 @@ moe_status moe_combine(const moe_shape* shape, const float* y_perm, const int32_
                        void* out, void* stream);
 
 /*
+ * For tools that attribute time or bytes to the two kernels of the expert FFN (the paper's compute-bound and
+ * memory-bound experts, Section 3.1): the smallest number of rows with which an expert's rows are run by the
+ * LDS-tiled kernel rather than the weight-streaming one in a call where the experts have `rows_host[e]` rows
+ * (HOST array [E]; 0 for experts that are empty or masked out).  It is 128, or one more than a streaming tile
+ * holds when the experts of 128 rows and more already fill the tiled kernel for a round; 0 when the shape
+ * never uses the tiled kernel (fp32, or fewer than 128 tokens) or on invalid arguments.  The current device's
+ * size enters (as in the calls themselves).
+ */
+int32_t moe_tiled_kernel_min_rows(const moe_shape* shape, const int32_t* rows_host);
+
+/*
  * Profiling aid for callers that time the kernels of the expert FFN separately (the paper reasons
  * about an expert's cost product by product, Section 2.2 and Eq. 3-4).  `events` is a HOST array of
  * five hipEvent_t created by the caller (entries may be NULL), or NULL to stop.  Until the next call,

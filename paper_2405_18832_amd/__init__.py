@@ -22,7 +22,7 @@ MOE_MAX_K, MOE_MAX_E = 8, 1024
 
 EXPORTS = ["moe_init", "moe_noalloc_max_workspace", "moe_layer_forward_noalloc",
            "moe_status_string", "moe_workspace_bytes", "moe_packed_weight_bytes", "moe_pack_weights",
-           "moe_set_profile_events",
+           "moe_set_profile_events", "moe_tiled_kernel_min_rows",
            "moe_parameter_movement_bytes", "moe_activation_movement_bytes", "moe_plan_devices", "moe_fetch_experts", "moe_tune_alpha",
            "moe_route", "moe_select_hot", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_biased", "moe_combine",
            "moe_layer_forward", "moe_layer_forward_biased"]
@@ -61,6 +61,8 @@ def load() -> ctypes.CDLL:
     lib.moe_init.argtypes = []
     lib.moe_noalloc_max_workspace.restype = sz
     lib.moe_noalloc_max_workspace.argtypes = []
+    lib.moe_tiled_kernel_min_rows.restype = ctypes.c_int32
+    lib.moe_tiled_kernel_min_rows.argtypes = [ctypes.POINTER(moe_shape), ctypes.POINTER(ctypes.c_int32)]
     lib.moe_layer_forward_noalloc.restype = ctypes.c_int
     lib.moe_layer_forward_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.moe_status_string.restype = ctypes.c_char_p
@@ -157,6 +159,12 @@ def moe_layer_forward_noalloc(shape, x, w_gate, gate_bias, w1, w2, mask, H, out,
     _check(load().moe_layer_forward_noalloc(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(w1),
                                             _ptr(w2), _ptr(mask), int(H), _ptr(out), _stream(stream)),
            "moe_layer_forward_noalloc")
+
+
+def moe_tiled_kernel_min_rows(shape: moe_shape, rows) -> int:
+    """`rows`: per-expert row counts of the call (a sequence of E ints, 0 for experts that do not run)."""
+    arr = (ctypes.c_int32 * len(rows))(*[int(r) for r in rows])
+    return int(load().moe_tiled_kernel_min_rows(ctypes.byref(shape), arr))
 
 
 def moe_workspace_bytes(shape: moe_shape) -> int:

@@ -103,6 +103,17 @@ size_t moe_packed_weight_bytes(const moe_shape* shape) {
     return static_cast<size_t>(shape->E) * shape->d_model * shape->d_ff * elem_size(shape->dtype);
 }
 
+int32_t moe_tiled_kernel_min_rows(const moe_shape* shape, const int32_t* rows_host) {
+    if (check_shape(shape) != MOE_OK || rows_host == nullptr) return 0;
+    (void)ensure_ready();                                   // the device's CU count; a default stands in without one
+    const TileLists l = ffn_tile_lists(*shape, nullptr, nullptr, nullptr, nullptr);
+    if (l.big_min <= 0) return 0;
+    int big_tiles = 0;
+    for (int e = 0; e < shape->E; ++e)
+        if (rows_host[e] >= l.big_min) big_tiles += (rows_host[e] + kBigTileRows - 1) / kBigTileRows;
+    return tiled_min_rows(big_tiles, l.small_rows, l.join_tiles);
+}
+
 void moe_set_profile_events(void* const* events) {
     set_profile_events(reinterpret_cast<const hipEvent_t*>(events));
 }

@@ -54,6 +54,15 @@ struct Tile {
 // kBigTileRows rows); smaller experts are weight-streaming work.
 constexpr int kBigTileRows = 256;
 constexpr int kBigMinRows = 128;
+// Experts between one streaming tile and kBigMinRows rows would have their weights streamed once per
+// streaming tile; as one mostly empty tile of the tiled kernel they cost about what a single pass over their
+// weights costs -- as long as the tiled kernel has whole rounds of units to run anyway, which hide the one
+// more unit per column tile.  They join the large experts when the tiles of the experts with kBigMinRows rows
+// already number `join_tiles` (the host's figure: one full round of units in the narrower product); with
+// fewer, an under-filled tiled kernel would only get longer.
+inline __host__ __device__ int tiled_min_rows(int big_tiles_at_min, int small_rows, int join_tiles) {
+    return (join_tiles > 0 && big_tiles_at_min >= join_tiles) ? small_rows + 1 : kBigMinRows;
+}
 // The LDS-tiled kernel cuts the units of its last, partly filled round along K; the parts leave fp32
 // partial tiles (kBigTileRows x 256) in the workspace and are handed out through a counter.
 constexpr int kSplitSlots = 256;        // partial tiles in the workspace
@@ -128,6 +137,7 @@ struct TileLists {
     float* partials;       // kSplitSlots partial tiles (nullptr when big_min == 0)
     int small_rows;        // rows per small tile
     int big_min;           // experts with >= big_min rows are "big"; 0 = none
+    int join_tiles;        // tiles of big experts from which the mid-sized experts join them (tiled_min_rows); 0 = never
 };
 
 #ifdef __HIPCC__
@@ -189,7 +199,16 @@ __device__ __forceinline__ int block_scan_1024(int v, int32_t* tmp) {
 // Called by all 1024 threads of a block, thread e owning expert e (row0, m rows; m = 0 when the
 // expert is empty or masked out).  `scan` is an LDS array of MOE_MAX_E ints.
 __device__ __forceinline__ void emit_tiles(int e, int row0, int m, const TileLists tl, int32_t* scan) {
-    const bool big = tl.big_min > 0 && m >= tl.big_min;
+    int min_rows = tl.big_min;
+    if (tl.big_min > 0 && tl.join_tiles > 0) {
+        // tiles of the experts that are large in any case, summed over the block
+        const int incl = block_scan_1024(m >= tl.big_min ? (m + kBigTileRows - 1) / kBigTileRows : 0, scan);
+        __syncthreads();
+        if (threadIdx.x == 1023) scan[16] = incl;
+        __syncthreads();
+        min_rows = tiled_min_rows(scan[16], tl.small_rows, tl.join_tiles);
+    }
+    const bool big = tl.big_min > 0 && m >= min_rows;
     for (int pass = 0; pass < 2; ++pass) {
         const int rows = pass == 0 ? tl.small_rows : kBigTileRows;
         const bool mine = (pass == 1) == big;
@@ -323,6 +342,7 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
 hipError_t launch_place(const moe_shape& s, const int32_t* idx, const int32_t* offsets, const int32_t* chunk_base,
                         int32_t* perm, int32_t* inv_perm, int32_t* tokmap, int chunk, hipStream_t st);
 int ffn_tile_rows(const moe_shape& s);
+int tiled_join_tiles(const moe_shape& s);
 hipError_t launch_expert_products(const moe_shape& s, const void* act, const int32_t* rowmap, bool act_kmajor,
                                   const void* w1, const void* w2, const float* b1, const float* b2, float* y_perm,
                                   void* h_ws, const TileLists& lists, const FoldOut& fold, hipStream_t st);

@@ -704,7 +704,15 @@ TileLists ffn_tile_lists(const moe_shape& s, Tile* small_ws, Tile* big_ws, int32
     // a large expert needs kBigMinRows rows, and an expert holds at most T rows
     l.big_min = (s.dtype == MOE_BF16 && s.T >= kBigMinRows) ? kBigMinRows : 0;
     l.partials = l.big_min > 0 ? partials_ws : nullptr;
+    l.join_tiles = l.big_min > 0 ? tiled_join_tiles(s) : 0;
     return l;
+}
+
+// one full round of the tiled kernel's units in the product with the fewer column tiles
+int tiled_join_tiles(const moe_shape& s) {
+    const int narrow = s.d_model < s.d_ff ? s.d_model : s.d_ff;
+    const int col_tiles = (narrow + 255) / 256;
+    return (tile_product_grid() + col_tiles - 1) / col_tiles;
 }
 
 // the two grouped products over existing tile lists

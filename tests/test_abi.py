@@ -200,3 +200,26 @@ def test_tune_alpha_matches_the_oracle():
     assert status(bw_a=0.0) == moe.MOE_ERR_INVALID_ARG and status(alpha=float("nan")) == moe.MOE_ERR_INVALID_ARG
     assert status(tt=(ctypes.c_double * 4)(1.0, 0.0, 3.0, 4.0)) == moe.MOE_ERR_INVALID_ARG
     assert status(a=(ctypes.c_int32 * 2)(3, -1)) == moe.MOE_ERR_INVALID_ARG
+
+
+def test_tiled_kernel_min_rows():
+    """Host arithmetic: from how many rows on an expert is run by the LDS-tiled kernel.  128, or one more than a
+    streaming tile (64 rows) once the experts of 128 rows and more fill a round of the tiled kernel's 256 blocks
+    in the narrower product (d_model / 256 column tiles)."""
+    s = shape(T=16384, d_model=2048, d_ff=8192, E=128, k=2)          # 8 column tiles: 32 row tiles make a round
+    rows = [0] * 128
+    assert moe.moe_tiled_kernel_min_rows(s, rows) == 128
+    rows[0] = 31 * 256                                               # 31 tiles
+    assert moe.moe_tiled_kernel_min_rows(s, rows) == 128
+    rows[1] = 129                                                    # the 32nd
+    assert moe.moe_tiled_kernel_min_rows(s, rows) == 65
+    rows[1] = 127                                                    # not large by itself: still 31
+    assert moe.moe_tiled_kernel_min_rows(s, rows) == 128
+    s2 = shape(T=4096, d_model=1024, d_ff=4096, E=128, k=1)          # 4 column tiles: 64 row tiles
+    rows = [256] * 63 + [0] * 65
+    assert moe.moe_tiled_kernel_min_rows(s2, rows) == 128
+    rows[63] = 1000
+    assert moe.moe_tiled_kernel_min_rows(s2, rows) == 65
+    # shapes that never use the tiled kernel
+    assert moe.moe_tiled_kernel_min_rows(shape(T=64), [10] * 8) == 0
+    assert moe.moe_tiled_kernel_min_rows(shape(T=4096, dtype="f32"), [512] * 8) == 0
