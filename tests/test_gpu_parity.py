@@ -26,7 +26,7 @@ from oracle import moe_oracle as orc
 
 pytestmark = pytest.mark.gpu
 
-TOL = 1e-2               # spec bar
+TOL = 1e-2               # the bar for values: max relative error against the oracle
 TOL_EXACT_ELEM = 1.5e-2  # element-wise against the never-rounding oracle (see the module docstring)
 TOL_F32 = 1e-5
 MARGIN = 1e-4
