@@ -80,12 +80,12 @@ class HipEvents:
 TRAFFIC_SOURCES = {"ffn.hip": "1011bc0bfcb93ea3", "ffn_tile.hip": "436f9bad48effd6a",
                    "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "7306a852dfe63120"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316551992, ("switch_base", "stream_w2"): 320347734,
-    ("switch_large_skew", "stream_w1"): 68334158, ("switch_large_skew", "stream_w2"): 141349257,
-    ("switch_large_skew", "tile_w1"): 90880593, ("switch_large_skew", "tile_w2"): 133076322,
-    ("nllb_decode", "stream_w1"): 1643608457, ("nllb_decode", "stream_w2"): 1645583143,
-    ("nllb_prefill_skew", "stream_w1"): 913807298, ("nllb_prefill_skew", "stream_w2"): 972058691,
-    ("nllb_prefill_skew", "tile_w1"): 2569030516, ("nllb_prefill_skew", "tile_w2"): 2386985079,
+    ("switch_base", "stream_w1"): 316541237, ("switch_base", "stream_w2"): 320341132,
+    ("switch_large_skew", "stream_w1"): 68335790, ("switch_large_skew", "stream_w2"): 141349935,
+    ("switch_large_skew", "tile_w1"): 90879139, ("switch_large_skew", "tile_w2"): 133077718,
+    ("nllb_decode", "stream_w1"): 1643612752, ("nllb_decode", "stream_w2"): 1645583552,
+    ("nllb_prefill_skew", "stream_w1"): 913813651, ("nllb_prefill_skew", "stream_w2"): 972057594,
+    ("nllb_prefill_skew", "tile_w1"): 2567409061, ("nllb_prefill_skew", "tile_w2"): 2388712231,
 }
 
 
