@@ -498,8 +498,21 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
         for (int i = 0; i < tl.rows; ++i) {
             const int src = rowmap ? rowmap[tl.row0 + i] : tl.row0 + i;
             const float* ar = act + static_cast<size_t>(src) * K;
-            float s = 0.f;
-            for (int c = 0; c < K; ++c) s = fmaf(ar[c], wr[c], s);
+            // four running sums over c mod 4 (16-byte loads, four independent chains), added pairwise at the end
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int c = 0;
+            if ((K & 3) == 0) {                            // rows of x, h and the weights are then 16-byte aligned
+                for (; c < K; c += 4) {
+                    const float4 a = *reinterpret_cast<const float4*>(ar + c);
+                    const float4 b = *reinterpret_cast<const float4*>(wr + c);
+                    s0 = fmaf(a.x, b.x, s0);
+                    s1 = fmaf(a.y, b.y, s1);
+                    s2 = fmaf(a.z, b.z, s2);
+                    s3 = fmaf(a.w, b.w, s3);
+                }
+            }
+            for (; c < K; ++c) s0 = fmaf(ar[c], wr[c], s0);
+            float s = (s0 + s1) + (s2 + s3);
             if (bias) s += bias[static_cast<size_t>(tl.expert) * N + n];
             outp[static_cast<size_t>(tl.row0 + i) * N + n] = FIRST ? activate(s, activation) : s;
         }
