@@ -77,15 +77,15 @@ class HipEvents:
 # HBM-side bytes per launch of the expert-FFN kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and commands: profiles/<workload>_full_layer.txt).  Valid only for the kernel sources they
 # were taken with: reported as null once one of the sources below has changed.
-TRAFFIC_SOURCES = {"ffn.hip": "1011bc0bfcb93ea3", "ffn_tile.hip": "436f9bad48effd6a",
+TRAFFIC_SOURCES = {"ffn.hip": "3244c151d56e3a52", "ffn_tile.hip": "436f9bad48effd6a",
                    "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "7306a852dfe63120"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316541237, ("switch_base", "stream_w2"): 320341132,
-    ("switch_large_skew", "stream_w1"): 68335790, ("switch_large_skew", "stream_w2"): 141349935,
-    ("switch_large_skew", "tile_w1"): 90879139, ("switch_large_skew", "tile_w2"): 133077718,
-    ("nllb_decode", "stream_w1"): 1643612752, ("nllb_decode", "stream_w2"): 1645583552,
-    ("nllb_prefill_skew", "stream_w1"): 913813651, ("nllb_prefill_skew", "stream_w2"): 972057594,
-    ("nllb_prefill_skew", "tile_w1"): 2567409061, ("nllb_prefill_skew", "tile_w2"): 2388712231,
+    ("switch_base", "stream_w1"): 316551071, ("switch_base", "stream_w2"): 320348425,
+    ("switch_large_skew", "stream_w1"): 68334260, ("switch_large_skew", "stream_w2"): 141347322,
+    ("switch_large_skew", "tile_w1"): 90886430, ("switch_large_skew", "tile_w2"): 133074786,
+    ("nllb_decode", "stream_w1"): 1643609071, ("nllb_decode", "stream_w2"): 1645574348,
+    ("nllb_prefill_skew", "stream_w1"): 913810469, ("nllb_prefill_skew", "stream_w2"): 972050408,
+    ("nllb_prefill_skew", "tile_w1"): 2561593287, ("nllb_prefill_skew", "tile_w2"): 2391665482,
 }
 
 
