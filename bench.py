@@ -80,12 +80,12 @@ class HipEvents:
 TRAFFIC_SOURCES = {"ffn.hip": "3244c151d56e3a52", "ffn_tile.hip": "436f9bad48effd6a",
                    "tile_schedule.hpp": "9fe1793c9c6ad92e", "common.hpp": "7306a852dfe63120"}
 TRAFFIC_BYTES = {
-    ("switch_base", "stream_w1"): 316551071, ("switch_base", "stream_w2"): 320348425,
-    ("switch_large_skew", "stream_w1"): 68334260, ("switch_large_skew", "stream_w2"): 141347322,
-    ("switch_large_skew", "tile_w1"): 90886430, ("switch_large_skew", "tile_w2"): 133074786,
-    ("nllb_decode", "stream_w1"): 1643609071, ("nllb_decode", "stream_w2"): 1645574348,
-    ("nllb_prefill_skew", "stream_w1"): 913810469, ("nllb_prefill_skew", "stream_w2"): 972050408,
-    ("nllb_prefill_skew", "tile_w1"): 2561593287, ("nllb_prefill_skew", "tile_w2"): 2391665482,
+    ("switch_base", "stream_w1"): 316526015, ("switch_base", "stream_w2"): 320342552,
+    ("switch_large_skew", "stream_w1"): 68335790, ("switch_large_skew", "stream_w2"): 141349222,
+    ("switch_large_skew", "tile_w1"): 90878013, ("switch_large_skew", "tile_w2"): 133077616,
+    ("nllb_decode", "stream_w1"): 1643615820, ("nllb_decode", "stream_w2"): 1645576598,
+    ("nllb_prefill_skew", "stream_w1"): 913815377, ("nllb_prefill_skew", "stream_w2"): 972053271,
+    ("nllb_prefill_skew", "tile_w1"): 2556990570, ("nllb_prefill_skew", "tile_w2"): 2389242192,
 }
 
 
